@@ -1,0 +1,429 @@
+/*
+ * natcomp_oracle.c -- plain CPU oracle for natural compression C_nat, natural
+ * dithering D_nat^{p,s}, their decoders and the n-worker decode-and-sum.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement
+ * of what the GPU library must compute.  It shares no code with the HIP path
+ * and the product never calls it: only the tests, the smoke check and the
+ * benchmark's cpu_baseline leg load it.
+ *
+ * Every routine is a scalar loop over elements in index order.  The only
+ * concession to speed is an OpenMP "parallel for" over independent elements
+ * (each element's result depends on its own index only), which changes no
+ * arithmetic and no order of floating-point accumulation: all reductions
+ * (norms, sums over workers) are sequential per output value.
+ *
+ * Sources, by routine:
+ *   orc_nat_round        Sec. 2, Def. 1 and the binary32 derivation ("From 32 to 9 bits"):
+ *                        P(exponent + 1) = m, P(mantissa dropped) = 1 - m.
+ *   orc_nat_encode       the same rule element-wise; 1 sign + 8 exponent bits per entry.
+ *   orc_nat_decode       sign and exponent kept, mantissa zero.
+ *   orc_pnorm            Sec. 3, ||x||_p = (sum |x_i|^p)^(1/p), 1 <= p <= inf.
+ *   orc_dither_level     Sec. 3, Def. 3 (general dithering) with the natural level set
+ *                        {0, 2^(1-s), ..., 1/2, 1}.
+ *   orc_dither_encode    y_i = |x_i| / ||x||_p, xi(y_i), sign(x_i); norm per caller segment.
+ *   orc_dither_decode    ||x||_p * sign * level.
+ *   orc_aggregate_*      Algorithm 1, the master's sum over workers of the decompressed updates.
+ *   orc_philox4x32_10    Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
+ *                        as 1, 2, 3" (SC'11), Philox-4x32 with 10 rounds.  The paper only
+ *                        asks for a Bernoulli draw per element; the generator, its keying by
+ *                        (seed, worker, index) and the 32-bit comparison are this build's choice.
+ *
+ * Parity status: every arithmetic rule here is pinned by tests against the
+ * paper's worked examples, exact probabilities by exhaustive enumeration of
+ * the random word, closed-form moments and brute force.  The byte/bit packing
+ * of the code planes is a free choice the paper does not fix: "parity
+ * unpinned" for the layout itself (it is checked only for self-consistency:
+ * decode(encode) and GPU bytes == oracle bytes).
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------------ */
+/* Random words                                                             */
+/* ------------------------------------------------------------------------ */
+
+/* One Philox-4x32 bijection with 10 rounds.  Round: with products
+ * P0 = M0*c0 and P1 = M1*c2 (32x32 -> 64 bits),
+ *   (c0, c1, c2, c3) <- (hi(P1)^c1^k0, lo(P1), hi(P0)^c3^k1, lo(P0)),
+ * then the key is bumped by the Weyl constants. */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    const uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)M0 * c0;
+        uint64_t p1 = (uint64_t)M1 * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += W0; k1 += W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Domains keep the streams of different operators apart. */
+enum { ORC_DOMAIN_NAT = 0, ORC_DOMAIN_DITHER = 1 };
+
+/* The 32-bit uniform word of global element g: the counter is (g/4, worker,
+ * domain), the key is the seed, and the element takes output word g mod 4.
+ * It depends on nothing but (seed, worker, domain, g). */
+uint32_t orc_random_word(uint64_t seed, uint32_t worker, uint32_t domain, uint64_t g)
+{
+    uint64_t q = g >> 2;
+    uint32_t ctr[4] = { (uint32_t)q, (uint32_t)(q >> 32), worker, domain };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    orc_philox4x32_10(ctr, key, out);
+    return out[g & 3];
+}
+
+static uint32_t f32_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+static float bits_f32(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+
+/* ------------------------------------------------------------------------ */
+/* Natural compression                                                      */
+/* ------------------------------------------------------------------------ */
+
+/* The rounding rule on one binary32 value with bits u = (sign, e, m) and one
+ * uniform 32-bit word r.  t = (-1)^sign 2^(e-127) (1 + m/2^23); it goes to
+ * exponent e+1 with probability m/2^23 and keeps exponent e (mantissa dropped)
+ * otherwise.  r/2^32 < m/2^23  <=>  r < m * 2^9, an integer comparison.
+ * m = 0 (zero or an exact power of two) never moves.  Returns the new 8-bit
+ * exponent field; 255 (the Inf/NaN exponent) is an absorbing ceiling. */
+uint32_t orc_nat_round(uint32_t u, uint32_t r)
+{
+    uint32_t e = (u >> 23) & 255u;
+    uint64_t m = u & 0x7FFFFFu;
+    uint32_t up = ((uint64_t)r < (m << 9)) ? 1u : 0u;
+    uint32_t e_new = e + up;
+    return e_new > 255u ? 255u : e_new;
+}
+
+/* Exhaustive count of "exponent + 1" outcomes over all 2^32 words r. */
+uint64_t orc_nat_count_up(uint32_t u)
+{
+    uint32_t e = (u >> 23) & 255u;
+    uint64_t count = 0;
+#pragma omp parallel for reduction(+ : count)
+    for (int64_t r = 0; r < ((int64_t)1 << 32); ++r)
+        count += (orc_nat_round(u, (uint32_t)r) != e);
+    return count;
+}
+
+/* x[0..d): exponent plane exp_out[i] = new exponent field of x[i];
+ * sign plane: bit (i mod 8) of sign_out[i/8] = sign bit of x[i]; the unused
+ * high bits of the last sign byte are zero.  Element i draws the word of
+ * global index index_offset + i. */
+void orc_nat_encode(const float *x, uint64_t d, uint64_t seed, uint32_t worker,
+                    uint64_t index_offset, uint8_t *exp_out, uint8_t *sign_out)
+{
+    uint64_t nsign = (d + 7) / 8;
+    memset(sign_out, 0, nsign);
+#pragma omp parallel for
+    for (int64_t byte = 0; byte < (int64_t)nsign; ++byte) {
+        uint8_t sb = 0;
+        for (int bit = 0; bit < 8; ++bit) {
+            uint64_t i = (uint64_t)byte * 8 + bit;
+            if (i >= d) break;
+            uint32_t u = f32_bits(x[i]);
+            uint32_t r = orc_random_word(seed, worker, ORC_DOMAIN_NAT, index_offset + i);
+            exp_out[i] = (uint8_t)orc_nat_round(u, r);
+            sb |= (uint8_t)((u >> 31) << bit);
+        }
+        sign_out[byte] = sb;
+    }
+}
+
+/* The decoded value has the stored sign and exponent and a zero mantissa. */
+static float nat_value(const uint8_t *exp, const uint8_t *sign, uint64_t i)
+{
+    uint32_t s = (sign[i >> 3] >> (i & 7)) & 1u;
+    return bits_f32((s << 31) | ((uint32_t)exp[i] << 23));
+}
+
+void orc_nat_decode(const uint8_t *exp, const uint8_t *sign, uint64_t d, float *out)
+{
+#pragma omp parallel for
+    for (int64_t i = 0; i < (int64_t)d; ++i)
+        out[i] = nat_value(exp, sign, (uint64_t)i);
+}
+
+/* ------------------------------------------------------------------------ */
+/* p-norm                                                                   */
+/* ------------------------------------------------------------------------ */
+
+/* ||x||_p over x[0..len), accumulated in double in index order.
+ * p = 1, 2 or INFINITY. Returns -1 for any other p. */
+double orc_pnorm(const float *x, uint64_t len, double p)
+{
+    double acc = 0.0;
+    if (isinf(p)) {
+        for (uint64_t i = 0; i < len; ++i) { double a = fabs((double)x[i]); if (a > acc) acc = a; }
+        return acc;
+    }
+    if (p == 1.0) {
+        for (uint64_t i = 0; i < len; ++i) acc += fabs((double)x[i]);
+        return acc;
+    }
+    if (p == 2.0) {
+        for (uint64_t i = 0; i < len; ++i) acc += (double)x[i] * (double)x[i];
+        return sqrt(acc);
+    }
+    return -1.0;
+}
+
+/* Segment s covers [seg_begin(s), seg_begin(s+1)).  Three ways to describe the
+ * segments: explicit offsets (num_segments+1 ascending values, first 0, last
+ * d); a fixed bucket length (offsets NULL, bucket > 0); or the whole vector
+ * (offsets NULL, bucket 0). */
+static uint64_t seg_count(uint64_t d, const uint64_t *offsets, uint32_t num_segments, uint32_t bucket)
+{
+    if (offsets) return num_segments;
+    if (bucket) return (d + bucket - 1) / bucket;
+    return 1;
+}
+static uint64_t seg_begin(uint64_t s, uint64_t d, const uint64_t *offsets, uint32_t num_segments, uint32_t bucket)
+{
+    uint64_t n = seg_count(d, offsets, num_segments, bucket);
+    if (s >= n) return d;
+    if (offsets) return offsets[s];
+    if (bucket) return s * (uint64_t)bucket;
+    return 0;
+}
+
+uint64_t orc_segment_count(uint64_t d, const uint64_t *offsets, uint32_t num_segments, uint32_t bucket)
+{
+    return seg_count(d, offsets, num_segments, bucket);
+}
+
+/* norms64[s] = ||x_segment s||_p in double. */
+void orc_pnorm_segments(const float *x, uint64_t d, const uint64_t *offsets, uint32_t num_segments,
+                        uint32_t bucket, double p, double *norms64)
+{
+    int64_t n = (int64_t)seg_count(d, offsets, num_segments, bucket);
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t s = 0; s < n; ++s) {
+        uint64_t b = seg_begin((uint64_t)s, d, offsets, num_segments, bucket);
+        uint64_t e = seg_begin((uint64_t)s + 1, d, offsets, num_segments, bucket);
+        norms64[s] = orc_pnorm(x + b, e - b, p);
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Natural dithering                                                        */
+/* ------------------------------------------------------------------------ */
+
+/* Levels l_s = 0 < l_{s-1} = 2^(1-s) < ... < l_1 = 1/2 < l_0 = 1.  Level code
+ * c in {0..s}: c = 0 is the level 0 and c >= 1 is 2^(c-s).  y in [0,1] is
+ * given by its binary32 bits yb (sign cleared); r is a uniform 32-bit word.
+ * With l_low <= y <= l_high adjacent levels, the result is l_high with
+ * probability (y - l_low) / (l_high - l_low):
+ *   y = 2^-k (1 + m/2^23), k <= s-1: between 2^-k and 2^(1-k), P(high) = m/2^23;
+ *   y below the lowest level 2^(1-s):  between 0 and 2^(1-s), P(high) = y 2^(s-1).
+ * Both are compared as integers against r/2^32; the second threshold is
+ * truncated to a multiple of 2^-32.  y >= 1 (possible by one rounding of the
+ * normalisation) is level 1; a subnormal or zero y is level 0. */
+uint32_t orc_dither_level(uint32_t yb, uint32_t s, uint32_t r)
+{
+    if (yb >= 0x3F800000u) return s;
+    uint32_t e_y = yb >> 23;
+    uint64_t m_y = yb & 0x7FFFFFu;
+    if (e_y == 0) return 0;
+    uint32_t k = 127u - e_y;                 /* 2^-k <= y < 2^(1-k), k >= 1 */
+    if (k <= s - 1) {
+        uint32_t up = ((uint64_t)r < (m_y << 9)) ? 1u : 0u;
+        return s - k + up;
+    }
+    uint32_t sh = k - (s - 1);               /* y 2^(s-1) = (1 + m/2^23) 2^-sh, sh >= 1 */
+    uint64_t threshold = (sh > 40) ? 0 : (((0x800000u | m_y) << 9) >> sh);
+    return ((uint64_t)r < threshold) ? 1u : 0u;
+}
+
+/* Exhaustive count, over all 2^32 words r, of outcomes equal to `code`. */
+uint64_t orc_dither_count(uint32_t yb, uint32_t s, uint32_t code)
+{
+    uint64_t count = 0;
+#pragma omp parallel for reduction(+ : count)
+    for (int64_t r = 0; r < ((int64_t)1 << 32); ++r)
+        count += (orc_dither_level(yb, s, (uint32_t)r) == code);
+    return count;
+}
+
+/* The normalisation: y = fl(|x| * fl(1/norm)), two correctly rounded binary32
+ * operations.  A norm below the smallest normal number (including 0) makes the
+ * whole segment code to zero (Def. 3: D(0) = 0). */
+float orc_dither_inv_norm(float norm)
+{
+    if (!(norm >= 1.17549435e-38f)) return 0.0f;
+    volatile float inv = 1.0f / norm;
+    return inv;
+}
+uint32_t orc_dither_y_bits(float x, float inv)
+{
+    volatile float y = fabsf(x) * inv;
+    return f32_bits(y) & 0x7FFFFFFFu;
+}
+
+/* Bits per level code: 1 <= s <= 127. */
+static uint32_t code_width(uint32_t s) { uint32_t b = 0; while ((1u << b) < s + 1) ++b; return b; }
+
+/* Packed layout, by code width b = ceil(log2(s+1)):
+ *   b <= 3: one fused nibble (sign << 3) | c per element, element i in byte i/2,
+ *           low nibble for even i; no sign plane.
+ *   b == 4: nibble plane with c (same nibble order) plus the sign plane of C_nat.
+ *   b >= 5: one byte c per element plus the sign plane.
+ * Planes are indexed by the element's position in x, not restarted per segment. */
+uint64_t orc_dither_code_bytes(uint64_t d, uint32_t s)
+{
+    return code_width(s) <= 4 ? (d + 1) / 2 : d;
+}
+uint64_t orc_dither_sign_bytes(uint64_t d, uint32_t s)
+{
+    return code_width(s) <= 3 ? 0 : (d + 7) / 8;
+}
+
+static void put_code(uint8_t *code, uint8_t *sign, uint64_t i, uint32_t s, uint32_t c, uint32_t sg)
+{
+    uint32_t b = code_width(s);
+    if (b <= 3) {
+        uint32_t nib = (sg << 3) | c;
+        code[i >> 1] |= (uint8_t)(nib << ((i & 1) * 4));
+    } else if (b == 4) {
+        code[i >> 1] |= (uint8_t)(c << ((i & 1) * 4));
+        sign[i >> 3] |= (uint8_t)(sg << (i & 7));
+    } else {
+        code[i] = (uint8_t)c;
+        sign[i >> 3] |= (uint8_t)(sg << (i & 7));
+    }
+}
+static void get_code(const uint8_t *code, const uint8_t *sign, uint64_t i, uint32_t s, uint32_t *c, uint32_t *sg)
+{
+    uint32_t b = code_width(s);
+    if (b <= 3) {
+        uint32_t nib = (code[i >> 1] >> ((i & 1) * 4)) & 15u;
+        *c = nib & 7u; *sg = nib >> 3;
+    } else if (b == 4) {
+        *c = (code[i >> 1] >> ((i & 1) * 4)) & 15u;
+        *sg = (sign[i >> 3] >> (i & 7)) & 1u;
+    } else {
+        *c = code[i];
+        *sg = (sign[i >> 3] >> (i & 7)) & 1u;
+    }
+}
+
+/* norms[s] is the binary32 norm of segment s that the encoder normalises by
+ * (the caller computes it: orc_pnorm_segments rounded to float, or the norm
+ * another implementation produced).  Writes the packed planes. */
+void orc_dither_encode(const float *x, uint64_t d, const uint64_t *offsets, uint32_t num_segments,
+                       uint32_t bucket, uint32_t s, const float *norms, uint64_t seed, uint32_t worker,
+                       uint64_t index_offset, uint8_t *code_out, uint8_t *sign_out)
+{
+    memset(code_out, 0, orc_dither_code_bytes(d, s));
+    if (orc_dither_sign_bytes(d, s)) memset(sign_out, 0, orc_dither_sign_bytes(d, s));
+    uint64_t n = seg_count(d, offsets, num_segments, bucket);
+    /* sequential over elements: neighbouring elements share bytes */
+    for (uint64_t sgm = 0; sgm < n; ++sgm) {
+        uint64_t b = seg_begin(sgm, d, offsets, num_segments, bucket);
+        uint64_t e = seg_begin(sgm + 1, d, offsets, num_segments, bucket);
+        float inv = orc_dither_inv_norm(norms[sgm]);
+        for (uint64_t i = b; i < e; ++i) {
+            uint32_t yb = orc_dither_y_bits(x[i], inv);
+            uint32_t r = orc_random_word(seed, worker, ORC_DOMAIN_DITHER, index_offset + i);
+            uint32_t c = orc_dither_level(yb, s, r);
+            put_code(code_out, sign_out, i, s, c, f32_bits(x[i]) >> 31);
+        }
+    }
+}
+
+/* Level value times norm: c = 0 gives a signed zero, c >= 1 gives
+ * fl(norm * 2^(c-s)) with the sign applied (exact unless it underflows). */
+static float dither_value(float norm, uint32_t s, uint32_t c, uint32_t sg)
+{
+    float mag = 0.0f;
+    if (c > 0) {
+        volatile float v = norm * ldexpf(1.0f, (int)c - (int)s);
+        mag = v;
+    }
+    return sg ? -mag : mag;
+}
+
+void orc_dither_decode(const float *norms, const uint8_t *code, const uint8_t *sign, uint64_t d,
+                       const uint64_t *offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
+                       float *out)
+{
+    uint64_t n = seg_count(d, offsets, num_segments, bucket);
+    for (uint64_t sgm = 0; sgm < n; ++sgm) {
+        uint64_t b = seg_begin(sgm, d, offsets, num_segments, bucket);
+        uint64_t e = seg_begin(sgm + 1, d, offsets, num_segments, bucket);
+        for (uint64_t i = b; i < e; ++i) {
+            uint32_t c, sg;
+            get_code(code, sign, i, s, &c, &sg);
+            out[i] = dither_value(norms[sgm], s, c, sg);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Sum over workers                                                         */
+/* ------------------------------------------------------------------------ */
+
+/* Worker w's planes start at exp + w*exp_stride and sign + w*sign_stride (bytes).
+ * out64[i]  = sum over w of the decoded values, in double.
+ * out32[i]  = the same sum taken left to right in binary32 (w = 0, 1, ...),
+ *             starting from the first worker's value.
+ * abs64[i]  = sum over w of |decoded value|, the scale a tolerance is relative to.
+ * Any of the three outputs may be NULL. */
+void orc_aggregate_nat(const uint8_t *exp, uint64_t exp_stride, const uint8_t *sign, uint64_t sign_stride,
+                       uint32_t n, uint64_t d, double *out64, float *out32, double *abs64)
+{
+#pragma omp parallel for
+    for (int64_t i = 0; i < (int64_t)d; ++i) {
+        double acc64 = 0.0, acca = 0.0;
+        volatile float acc32 = 0.0f;
+        for (uint32_t w = 0; w < n; ++w) {
+            float v = nat_value(exp + (uint64_t)w * exp_stride, sign + (uint64_t)w * sign_stride, (uint64_t)i);
+            acc64 += (double)v;
+            acca += fabs((double)v);
+            acc32 = (w == 0) ? v : acc32 + v;
+        }
+        if (out64) out64[i] = acc64;
+        if (out32) out32[i] = acc32;
+        if (abs64) abs64[i] = acca;
+    }
+}
+
+/* The same for dithering codes; worker w's norms start at norms + w*norm_stride (floats). */
+void orc_aggregate_dither(const float *norms, uint64_t norm_stride, const uint8_t *code, uint64_t code_stride,
+                          const uint8_t *sign, uint64_t sign_stride, uint32_t n, uint64_t d,
+                          const uint64_t *offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
+                          double *out64, float *out32, double *abs64)
+{
+    int64_t nseg = (int64_t)seg_count(d, offsets, num_segments, bucket);
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t sgm = 0; sgm < nseg; ++sgm) {
+        uint64_t b = seg_begin((uint64_t)sgm, d, offsets, num_segments, bucket);
+        uint64_t e = seg_begin((uint64_t)sgm + 1, d, offsets, num_segments, bucket);
+        for (uint64_t i = b; i < e; ++i) {
+            double acc64 = 0.0, acca = 0.0;
+            volatile float acc32 = 0.0f;
+            for (uint32_t w = 0; w < n; ++w) {
+                uint32_t c, sg;
+                get_code(code + (uint64_t)w * code_stride, sign ? sign + (uint64_t)w * sign_stride : NULL, i, s, &c, &sg);
+                float v = dither_value(norms[(uint64_t)w * norm_stride + (uint64_t)sgm], s, c, sg);
+                acc64 += (double)v;
+                acca += fabs((double)v);
+                acc32 = (w == 0) ? v : acc32 + v;
+            }
+            if (out64) out64[i] = acc64;
+            if (out32) out32[i] = acc32;
+            if (abs64) abs64[i] = acca;
+        }
+    }
+}

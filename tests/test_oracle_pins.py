@@ -1,0 +1,540 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU).
+
+Each test checks the oracle against something other than itself: values the paper
+prints, exact probabilities obtained by exhausting the random word, closed-form
+moments, numpy routines on the special cases that reduce to them, brute force.
+"""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from conftest import golden_lines
+
+TWO32 = 1 << 32
+
+
+def f32_bits(t):
+    return int(np.float32(t).view(np.uint32))
+
+
+def bits_f32(u):
+    return float(np.uint32(u).view(np.float32))
+
+
+# ----------------------------------------------------------------------------- Philox
+def test_philox_known_answers(oracle):
+    rows = golden_lines("philox4x32_10_kat.txt")
+    assert len(rows) == 3
+    for row in rows:
+        v = [int(h, 16) for h in row]
+        out = oracle.philox4x32_10(v[0:4], v[4:6])
+        assert [int(o) for o in out] == v[6:10]
+
+
+def test_random_word_layout(oracle):
+    """Element g takes word g mod 4 of the call with counter (lo(g/4), hi(g/4), worker, domain), key = seed."""
+    seed = 0x0123456789ABCDEF
+    for g in [0, 1, 2, 3, 4, 7, 1023, (1 << 34) + 5, (1 << 40) + 2]:
+        for worker, domain in [(0, 0), (3, 1), (7, 0)]:
+            q = g >> 2
+            ref = oracle.philox4x32_10([q & 0xFFFFFFFF, q >> 32, worker, domain], [seed & 0xFFFFFFFF, seed >> 32])
+            assert oracle.random_word(seed, worker, domain, g) == int(ref[g & 3])
+
+
+def test_random_words_look_uniform(oracle):
+    """Bit balance and distinct streams per worker/domain/seed (a wiring mistake that reuses a
+    word or ignores a field shows up here)."""
+    n = 20000
+    w = np.array([oracle.random_word(5, 0, 0, g) for g in range(n)], dtype=np.uint64)
+    for bit in range(32):
+        frac = float(((w >> np.uint64(bit)) & np.uint64(1)).mean())
+        assert abs(frac - 0.5) < 5 * 0.5 / math.sqrt(n)
+    assert len(set(w.tolist())) > n - 5
+    others = [
+        [oracle.random_word(5, 1, 0, g) for g in range(64)],
+        [oracle.random_word(5, 0, 1, g) for g in range(64)],
+        [oracle.random_word(6, 0, 0, g) for g in range(64)],
+        [oracle.random_word(5 + (1 << 32), 0, 0, g) for g in range(64)],
+    ]
+    base = w[:64].tolist()
+    for o in others:
+        assert sum(a == b for a, b in zip(base, o)) == 0
+
+
+# ------------------------------------------------------------------ natural compression
+def up_threshold(oracle, u):
+    """Smallest r for which the exponent is NOT incremented (the rule is 'up iff r < T'):
+    found by bisection after checking monotonicity on a sample."""
+    e = (u >> 23) & 255
+    rs = np.random.default_rng(u).integers(0, TWO32, 64).tolist() + [0, TWO32 - 1]
+    ups = sorted((r, oracle.nat_round(u, r) != e) for r in rs)
+    seen_down = False
+    for _, up in ups:
+        if not up:
+            seen_down = True
+        assert not (up and seen_down), "rule is not monotone in r"
+    if oracle.nat_round(u, 0) == e:
+        return 0
+    lo, hi = 0, TWO32           # up at lo, not up at hi (hi = 2^32 is the sentinel)
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        if oracle.nat_round(u, mid) != e:
+            lo = mid
+        else:
+            hi = mid
+    return hi
+
+
+def definition_probabilities(t):
+    """Def. 1 in exact rational arithmetic: (low, high, p_low) with |low| <= |t| <= |high|."""
+    ft = Fraction(abs(float(t)))
+    a = math.floor(math.log2(ft))
+    while Fraction(2) ** a > ft:
+        a -= 1
+    while Fraction(2) ** (a + 1) <= ft:
+        a += 1
+    low, high = Fraction(2) ** a, Fraction(2) ** (a + 1)
+    return low, high, (high - ft) / low
+
+
+def test_paper_worked_examples_exhaustive(oracle):
+    """All 2^32 random words: the count of 'up' outcomes gives the exact probability."""
+    for _, t, low, high, p_low in golden_lines("paper_examples.txt", "nat"):
+        t, low, high, p_low = float(t), float(low), float(high), Fraction(p_low)
+        u = f32_bits(t)
+        e = (u >> 23) & 255
+        count_up = oracle.nat_count_up(u)
+        assert Fraction(count_up, TWO32) == 1 - p_low
+        # the two outcomes are exactly the paper's values
+        sign = -1.0 if t < 0 else 1.0
+        assert sign * 2.0 ** (oracle.nat_round(u, TWO32 - 1) - 127) == low
+        assert sign * 2.0 ** (oracle.nat_round(u, 0) - 127) == high
+        assert oracle.nat_round(u, TWO32 - 1) == e and oracle.nat_round(u, 0) == e + 1
+
+
+def test_binary32_fields_of_paper_example(oracle):
+    (_, t, s, e, mn, md), = golden_lines("paper_examples.txt", "fields")
+    u = f32_bits(float(t))
+    assert u >> 31 == int(s) and (u >> 23) & 255 == int(e)
+    assert Fraction(u & 0x7FFFFF, 1 << 23) == Fraction(int(mn), int(md))
+    # P(up) = m (binary32 derivation), here 3/8
+    assert Fraction(up_threshold(oracle, u), TWO32) == Fraction(int(mn), int(md))
+
+
+def test_probability_matches_definition_on_random_values(oracle):
+    rng = np.random.default_rng(11)
+    ts = (rng.standard_normal(300) * np.exp2(rng.integers(-40, 20, 300))).astype(np.float32)
+    for t in ts:
+        if t == 0:
+            continue
+        u = f32_bits(t)
+        low, high, p_low = definition_probabilities(t)
+        assert Fraction(up_threshold(oracle, u), TWO32) == 1 - p_low
+        e = (u >> 23) & 255
+        assert Fraction(2) ** (e - 127) == low
+
+
+def test_unbiased_and_second_moment_closed_form(oracle):
+    """E C(t) = t and E C(t)^2 = 2^a (3|t| - 2^(a+1)) exactly, ratio <= 9/8 (Thm. 1 and its proof)."""
+    rng = np.random.default_rng(12)
+    ts = (rng.standard_normal(300) * np.exp2(rng.integers(-30, 30, 300))).astype(np.float32)
+    worst = Fraction(0)
+    for t in list(ts) + [bits_f32(0x3FAAAAAB), bits_f32(0x3FAAAAAA), 2.5, -2.75, 0.75]:
+        u = f32_bits(t)
+        e = (u >> 23) & 255
+        if e == 0:
+            continue
+        p_up = Fraction(up_threshold(oracle, u), TWO32)
+        lo_v, hi_v = Fraction(2) ** (e - 127), Fraction(2) ** (e - 126)
+        ft = Fraction(abs(float(t)))
+        assert (1 - p_up) * lo_v + p_up * hi_v == ft
+        second = (1 - p_up) * lo_v ** 2 + p_up * hi_v ** 2
+        assert second == lo_v * (3 * ft - 2 * lo_v)
+        assert second <= Fraction(9, 8) * ft ** 2
+        worst = max(worst, second / ft ** 2)
+    (_, tn, td, vn, vd), = golden_lines("paper_examples.txt", "ratio")
+    assert Fraction(int(tn), int(td)) == Fraction(4, 3)
+    assert float(Fraction(int(vn), int(vd)) - worst) < 1e-6      # 4/3 is not a binary32 number; its neighbour gets this close
+
+
+def test_pass_through_and_bracket(oracle):
+    """Zeros and exact powers of two never move, whatever the word; every other value lands on
+    one of its two bracketing powers of two with the sign kept."""
+    words = [0, 1, 0x7FFFFFFF, 0x80000000, TWO32 - 1] + np.random.default_rng(3).integers(0, TWO32, 50).tolist()
+    for e in [0, 1, 2, 100, 127, 128, 200, 254]:
+        for s in (0, 1):
+            u = (s << 31) | (e << 23)
+            for r in words:
+                assert oracle.nat_round(u, r) == e
+    rng = np.random.default_rng(4)
+    for t in (rng.standard_normal(200) * np.exp2(rng.integers(-100, 100, 200))).astype(np.float32):
+        u = f32_bits(t)
+        e = (u >> 23) & 255
+        if e in (0, 255) or (u & 0x7FFFFF) == 0:
+            continue
+        outs = {oracle.nat_round(u, r) for r in words}
+        assert outs <= {e, e + 1}
+        assert outs == {e, e + 1}          # r = 0 goes up (m > 0), r = 2^32-1 stays
+        assert 2.0 ** (e - 127) <= abs(float(t)) <= 2.0 ** (e - 126)
+
+
+def test_corner_cases_of_the_integer_rule(oracle):
+    # subnormal input: outcome 0 or the smallest normal, P(up) = m, still unbiased
+    u = 0x00400000                          # 2^-127
+    assert oracle.nat_round(u, TWO32 - 1) == 0 and oracle.nat_round(u, 0) == 1
+    assert Fraction(up_threshold(oracle, u), TWO32) == Fraction(1, 2)
+    # infinity and NaN keep exponent 255
+    for u in (0x7F800000, 0xFF800000, 0x7FC00000, 0x7FFFFFFF):
+        for r in (0, 12345, TWO32 - 1):
+            assert oracle.nat_round(u, r) == 255
+    # just below 2^128 may round up to the infinity exponent
+    assert oracle.nat_round(0x7F7FFFFF, 0) == 255 and oracle.nat_round(0x7F7FFFFF, TWO32 - 1) == 254
+
+
+def test_encode_decode_vectors(oracle):
+    from paper_1905_10988_amd import workloads
+    x = workloads.config1(d=5000, seed=1)
+    exp, sign = oracle.nat_encode(x, seed=9, worker=2)
+    y = oracle.nat_decode(exp, sign, x.size)
+    ax, ay = np.abs(x.astype(np.float64)), np.abs(y.astype(np.float64))
+    assert np.array_equal(np.signbit(x), np.signbit(y))
+    nz = ax > 0
+    assert np.all(ay[~nz] == 0)
+    lo = np.exp2(np.floor(np.log2(ax[nz])))
+    assert np.all((ay[nz] == lo) | (ay[nz] == 2 * lo))
+    pow2 = nz & (np.frexp(ax)[0] == 0.5)
+    assert pow2.sum() >= 40 and np.array_equal(y[pow2], x[pow2])
+    # plane layout: byte i of the exponent plane, bit i%8 of sign byte i//8
+    assert np.array_equal(exp, (y.view(np.uint32) >> 23).astype(np.uint8))
+    assert np.array_equal(np.unpackbits(sign, bitorder="little")[: x.size].astype(bool), np.signbit(x))
+    # an element's code depends on its global index only: slices with the right offset agree
+    for a, b in [(8, 4000), (13, 777), (4093, 5000)]:
+        e2, s2 = oracle.nat_encode(x[a:b], seed=9, worker=2, index_offset=a)
+        assert np.array_equal(e2, exp[a:b])
+        assert np.array_equal(oracle.nat_decode(e2, s2, b - a), y[a:b])
+    # other worker / seed: a different draw
+    e3, _ = oracle.nat_encode(x, seed=9, worker=3)
+    e4, _ = oracle.nat_encode(x, seed=10, worker=2)
+    assert 0.05 < np.mean(e3 != exp) < 0.6 and 0.05 < np.mean(e4 != exp) < 0.6
+
+
+def test_edge_values_roundtrip(oracle):
+    from paper_1905_10988_amd import workloads
+    x = workloads.edge_values()
+    exp, sign = oracle.nat_encode(x, seed=1)
+    y = oracle.nat_decode(exp, sign, x.size)
+    assert np.array_equal(np.signbit(x), np.signbit(y))
+    xb = x.view(np.uint32)
+    assert np.all((exp == ((xb >> 23) & 255)) | (exp == np.minimum(((xb >> 23) & 255) + 1, 255)))
+    assert np.all(np.isinf(y[np.isinf(x) | np.isnan(x)]))
+
+
+def test_tiny_d_all_outcomes(oracle):
+    """d = 3: enumerate the 2^3 outcomes with product probabilities; the operator is unbiased
+    and E||C(x)||^2 <= 9/8 ||x||^2 (Def. 2 with omega = 1/8)."""
+    x = np.array([2.5, -2.75, 0.75], np.float32)
+    ps, vals = [], []
+    for t in x:
+        u = f32_bits(t)
+        e = (u >> 23) & 255
+        p_up = Fraction(up_threshold(oracle, u), TWO32)
+        sgn = -1 if t < 0 else 1
+        ps.append((1 - p_up, p_up))
+        vals.append((sgn * Fraction(2) ** (e - 127), sgn * Fraction(2) ** (e - 126)))
+    mean = [Fraction(0)] * 3
+    second = Fraction(0)
+    total = Fraction(0)
+    for mask in range(8):
+        pr = Fraction(1)
+        out = []
+        for i in range(3):
+            b = (mask >> i) & 1
+            pr *= ps[i][b]
+            out.append(vals[i][b])
+        total += pr
+        for i in range(3):
+            mean[i] += pr * out[i]
+        second += pr * sum(o * o for o in out)
+    assert total == 1
+    assert mean == [Fraction(float(t)) for t in x]
+    norm2 = sum(Fraction(float(t)) ** 2 for t in x)
+    assert norm2 < second <= Fraction(9, 8) * norm2
+    # and the actual random draws realise only those outcomes
+    seen = set()
+    for seed in range(200):
+        e, s = oracle.nat_encode(x, seed=seed)
+        seen.add(tuple(oracle.nat_decode(e, s, 3).tolist()))
+    allowed = {(float(vals[0][a]), float(vals[1][b]), float(vals[2][c])) for a in (0, 1) for b in (0, 1) for c in (0, 1)}
+    assert seen <= allowed and len(seen) == 8
+
+
+def test_empirical_mean_and_second_moment_with_philox(oracle):
+    """Over many seeds the decoded mean converges to x (5 standard errors, per-draw variance
+    <= t^2/8) and the second-moment ratio stays below 9/8."""
+    rng = np.random.default_rng(21)
+    d, S = 2048, 1500
+    x = (rng.standard_normal(d) * np.exp2(rng.integers(-20, 4, d))).astype(np.float32)
+    acc = np.zeros(d)
+    acc2 = np.zeros(d)
+    for seed in range(S):
+        e, s = oracle.nat_encode(x, seed=seed, worker=seed % 5)
+        y = oracle.nat_decode(e, s, d).astype(np.float64)
+        acc += y
+        acc2 += y * y
+    mean, second = acc / S, acc2 / S
+    x64 = x.astype(np.float64)
+    se = np.abs(x64) * math.sqrt(1 / 8 / S)
+    assert np.all(np.abs(mean - x64) <= 5 * se + 1e-300)
+    assert second.sum() / (x64 ** 2).sum() <= 9 / 8
+    # per element: the empirical second moment sits on the closed form 2^a (3|t| - 2^(a+1));
+    # a draw of y^2 is L^2 or 4 L^2 (L = 2^a), so its standard deviation is at most 1.5 L^2
+    L = np.exp2(np.floor(np.log2(np.abs(x64))))
+    closed = L * (3 * np.abs(x64) - 2 * L)
+    assert np.all(np.abs(second - closed) <= 5.5 * 1.5 * L ** 2 / math.sqrt(S))
+    # the mean of the standardised errors is itself centred (no systematic drift)
+    z = (mean - x64)[se > 0] / se[se > 0]
+    assert abs(z.mean()) < 5 / math.sqrt(z.size)
+
+
+# ----------------------------------------------------------------------------- norms
+def test_pnorm_closed_forms_and_numpy(oracle):
+    x = np.array([3.0, -4.0], np.float32)
+    assert oracle.pnorm(x, 2) == 5.0 and oracle.pnorm(x, 1) == 7.0 and oracle.pnorm(x, math.inf) == 4.0
+    assert oracle.pnorm(np.zeros(5, np.float32), 2) == 0.0
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal(100003) * 1e-3).astype(np.float32)
+    x64 = x.astype(np.float64)
+    for p in (1, 2, math.inf):
+        ref = np.linalg.norm(x64, ord=p)
+        assert abs(oracle.pnorm(x, p) - ref) <= 1e-12 * ref
+    off = np.array([0, 64, 1000, 1000, 50000, 100003], np.uint64)
+    for p in (1, 2, math.inf):
+        got = oracle.pnorm_segments(x, p, offsets=off)
+        for j in range(5):
+            seg = x64[int(off[j]):int(off[j + 1])]
+            ref = np.linalg.norm(seg, ord=p) if seg.size else 0.0
+            assert abs(got[j] - ref) <= 1e-12 * max(ref, 1e-300)
+        got = oracle.pnorm_segments(x, p, bucket=8192)
+        assert got.size == 13
+        assert abs(got[12] - np.linalg.norm(x64[12 * 8192:], ord=p)) <= 1e-12 * got[12]
+        assert abs(oracle.pnorm_segments(x, p)[0] - np.linalg.norm(x64, ord=p)) <= 1e-12 * got.max() * 100
+
+
+# ------------------------------------------------------------------ natural dithering
+def level_value(s, c):
+    return Fraction(0) if c == 0 else Fraction(2) ** (c - s)
+
+
+def dither_threshold(oracle, yb, s):
+    """(low code, T) with outcome low+1 iff r < T; checks that only two adjacent codes occur."""
+    c_hi, c_lo = oracle.dither_level(yb, s, 0), oracle.dither_level(yb, s, TWO32 - 1)
+    assert c_hi - c_lo in (0, 1)
+    if c_hi == c_lo:
+        return c_lo, 0
+    lo, hi = 0, TWO32
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        if oracle.dither_level(yb, s, mid) == c_hi:
+            lo = mid
+        else:
+            hi = mid
+    return c_lo, hi
+
+
+def test_level_set_of_paper(oracle):
+    (row,) = golden_lines("paper_examples.txt", "levels")
+    s = int(row[1])
+    levels = [float(v) for v in row[2:]]
+    assert len(levels) == s + 1
+    norms = np.array([1.0], np.float32)
+    for c, lv in enumerate(levels):
+        code = np.array([c], np.uint8)          # s = 4: fused nibble, sign bit 3 clear
+        out = oracle.dither_decode(norms, code, None, 1, s)
+        assert out[0] == lv
+        code = np.array([c | 8], np.uint8)
+        assert oracle.dither_decode(norms, code, None, 1, s)[0] == -lv
+    # a value sitting exactly on a level stays there for every word
+    for c, lv in enumerate(levels):
+        for r in (0, 999, TWO32 - 1):
+            assert oracle.dither_level(f32_bits(lv), s, r) == c
+
+
+def test_dither_paper_example_exhaustive(oracle):
+    (_, s, y, low, high, p_high), = golden_lines("paper_examples.txt", "dither")
+    s, y, low, high, p_high = int(s), float(y), float(low), float(high), Fraction(p_high)
+    yb = f32_bits(y)
+    c_low = {float(level_value(s, c)): c for c in range(s + 1)}[low]
+    c_high = {float(level_value(s, c)): c for c in range(s + 1)}[high]
+    assert c_high == c_low + 1
+    n_high = oracle.dither_count(yb, s, c_high)
+    n_low = oracle.dither_count(yb, s, c_low)
+    assert n_high + n_low == TWO32
+    assert Fraction(n_high, TWO32) == p_high
+
+
+def test_dither_probabilities_match_definition(oracle):
+    """xi(y) = l_high w.p. (y - l_low)/(l_high - l_low) (Def. 3), exactly above the lowest
+    level and up to the 2^-32 truncation below it; hence E xi(y) = y."""
+    rng = np.random.default_rng(31)
+    for s in (1, 2, 3, 4, 8, 16, 40, 126, 127):
+        ys = np.concatenate([rng.uniform(0, 1, 40), np.exp2(-rng.uniform(0, 60, 40)), [1.0, 0.5, 2.0 ** (1 - min(s, 100))]])
+        for y in ys.astype(np.float32):
+            yb = f32_bits(y)
+            fy = Fraction(float(y))
+            c_lo, T = dither_threshold(oracle, yb, s)
+            if fy >= 1:
+                assert (c_lo, T) == (s, 0)
+                continue
+            l_lo, l_hi = level_value(s, c_lo), level_value(s, c_lo + 1)
+            assert l_lo <= fy < l_hi
+            p_exact = (fy - l_lo) / (l_hi - l_lo)
+            if c_lo >= 1:
+                assert Fraction(T, TWO32) == p_exact
+            else:
+                assert T == math.floor(p_exact * TWO32)
+            mean = l_lo + Fraction(T, TWO32) * (l_hi - l_lo)
+            assert abs(mean - fy) <= Fraction(1, TWO32) * l_hi
+    # y >= 1 is level 1, zero and subnormal y are level 0
+    assert oracle.dither_level(0x3F800001, 4, 0) == 4
+    assert oracle.dither_level(0, 4, 0) == 0 and oracle.dither_level(0x007FFFFF, 4, 0) == 0
+
+
+def test_dithering_tends_to_natural_compression(oracle):
+    """With a power-of-two norm and many levels the level picked is the exponent C_nat picks
+    from the same word (D_nat is a limited-precision C_nat, Sec. 3)."""
+    rng = np.random.default_rng(32)
+    s = 126
+    for t in (rng.uniform(0, 1, 300) * np.exp2(-rng.integers(0, 100, 300))).astype(np.float32):
+        u = f32_bits(t)
+        e = (u >> 23) & 255
+        if e < 2:
+            continue
+        for r in rng.integers(0, TWO32, 6).tolist() + [0, TWO32 - 1]:
+            c = oracle.dither_level(u, s, r)
+            assert c - s == oracle.nat_round(u, r) - 127
+
+
+def test_dither_normalisation(oracle):
+    assert oracle.dither_inv_norm(0.0) == 0.0
+    assert oracle.dither_inv_norm(1e-39) == 0.0           # subnormal norm: segment treated as zero
+    assert oracle.dither_inv_norm(4.0) == 0.25
+    assert oracle.dither_inv_norm(3.0) == float(np.float32(1.0) / np.float32(3.0))
+    inv = np.float32(oracle.dither_inv_norm(3.0))
+    for x in (0.7, -2.2, 3.0, 1e-20):
+        want = np.float32(abs(np.float32(x))) * inv
+        assert oracle.dither_y_bits(x, inv) == int(np.float32(want).view(np.uint32))
+
+
+def _dither_roundtrip(oracle, x, s, p, seed, offsets=None, bucket=0):
+    norms = oracle.pnorm_segments(x, p, offsets=offsets, bucket=bucket).astype(np.float32)
+    code, sign = oracle.dither_encode(x, s, norms, seed, offsets=offsets, bucket=bucket)
+    return norms, code, sign, oracle.dither_decode(norms, code, sign, x.size, s, offsets=offsets, bucket=bucket)
+
+
+def test_dither_vector_brackets_and_layouts(oracle):
+    rng = np.random.default_rng(33)
+    d = 3001
+    x = (rng.laplace(0, 1, d) * 1e-3).astype(np.float32)
+    x[5] = 0.0
+    x[6] = -0.0
+    off = np.array([0, 64, 65, 1000, 1000, d], np.uint64)
+    for s, p in [(4, math.inf), (8, 2), (3, 1), (20, 2), (1, math.inf), (127, math.inf)]:
+        for kw in ({}, {"bucket": 512}, {"offsets": off}):
+            norms, code, sign, y = _dither_roundtrip(oracle, x, s, p, seed=4, **kw)
+            assert code.size == ((d + 1) // 2 if s <= 15 else d)
+            assert sign.size == (0 if s <= 7 else (d + 7) // 8)
+            assert np.array_equal(np.signbit(y), np.signbit(x))
+            if "offsets" in kw:
+                seg = np.repeat(np.arange(5), np.diff(off.astype(np.int64)))
+            elif "bucket" in kw:
+                seg = np.arange(d) // 512
+            else:
+                seg = np.zeros(d, np.int64)
+            nrm = norms.astype(np.float64)[seg]
+            ratio = np.abs(y.astype(np.float64)) / nrm
+            yy = np.abs(x.astype(np.float64)) / nrm
+            # decoded magnitudes are levels times the norm, adjacent to the normalised input
+            levels = np.array([0.0] + [2.0 ** (c - s) for c in range(1, s + 1)])
+            idx = np.searchsorted(levels, ratio)
+            assert np.all(np.abs(levels[np.minimum(idx, s)] - ratio) <= 1e-6 * ratio + 1e-300)
+            lo = levels[np.maximum(np.searchsorted(levels, yy * (1 - 1e-6), side="right") - 1, 0)]
+            hi = levels[np.minimum(np.searchsorted(levels, yy * (1 + 1e-6), side="left"), s)]
+            assert np.all((ratio >= lo * (1 - 1e-6)) & (ratio <= hi * (1 + 1e-6)))
+    # a zero segment codes to zeros (Def. 3: D(0) = 0)
+    z = np.zeros(100, np.float32)
+    norms, code, sign, y = _dither_roundtrip(oracle, z, 8, 2, seed=1)
+    assert norms[0] == 0 and not code.any() and not y.any()
+
+
+def test_dither_unbiased_and_variance_bound(oracle):
+    """Thm. 4: E||D(x) - x||^2 <= omega ||x||^2 with omega = 1/8 + d^(1/r) 2^(1-s) min{1, d^(1/r) 2^(1-s)};
+    Gaussian x as in the empirical-variance appendix (smaller d to keep the test short)."""
+    rng = np.random.default_rng(34)
+    d, S = 10000, 120
+    x = rng.standard_normal(d).astype(np.float32)
+    x64 = x.astype(np.float64)
+    for p, s in [(2, 8), (math.inf, 4), (1, 12), (2, 3)]:
+        norms = oracle.pnorm_segments(x, p).astype(np.float32)
+        acc = np.zeros(d)
+        var = 0.0
+        for seed in range(S):
+            code, sign = oracle.dither_encode(x, s, norms, seed)
+            y = oracle.dither_decode(norms, code, sign, d, s).astype(np.float64)
+            acc += y
+            var += ((y - x64) ** 2).sum()
+        var /= S
+        r = min(p, 2)
+        a = d ** (1 / r) * 2.0 ** (1 - s)
+        omega = 1 / 8 + a * min(1.0, a)
+        assert var <= omega * (x64 ** 2).sum()
+        # unbiased: the mean error is small against the per-coordinate standard error
+        mean = acc / S
+        sd = math.sqrt(var / d / S)
+        assert abs((mean - x64).mean()) < 5 * sd / math.sqrt(d)
+        assert np.abs(mean - x64).max() < 8 * float(norms[0]) / math.sqrt(S)
+
+
+# ------------------------------------------------------------------ sum over workers
+def test_aggregate_against_numpy(oracle):
+    from paper_1905_10988_amd import workloads
+    d, n = 4099, 8
+    off = workloads.layer_offsets(d=d, num_layers=7, lo=64, hi=2000, seed=3)
+    exps, signs, dec = [], [], []
+    for w in range(n):
+        x = workloads.layered_gaussian(w, off, seed=77)
+        e, s = oracle.nat_encode(x, seed=5, worker=w)
+        exps.append(e)
+        signs.append(s)
+        dec.append(oracle.nat_decode(e, s, d))
+    o64, o32, oa = oracle.aggregate_nat(np.stack(exps), np.stack(signs), d)
+    dec = np.stack(dec)
+    assert np.array_equal(o64, dec.astype(np.float64).sum(axis=0))       # powers of two: the double sum is exact
+    seq = dec[0].copy()
+    for w in range(1, n):
+        seq = (seq + dec[w]).astype(np.float32)
+    assert np.array_equal(o32, seq)
+    assert np.array_equal(oa, np.abs(dec.astype(np.float64)).sum(axis=0))
+    assert np.all(np.abs(o32 - o64) <= 1e-5 * oa)
+
+    # dithering codes, bucketed, fused nibble (s = 4) and nibble + sign plane (s = 8)
+    for s, p in [(4, math.inf), (8, 2), (20, 1)]:
+        norms, codes, sgns, dec = [], [], [], []
+        for w in range(n):
+            x = workloads.bucketed_gaussian(w, d=d, bucket=512, seed=9)
+            nr = oracle.pnorm_segments(x, p, bucket=512).astype(np.float32)
+            c, sg = oracle.dither_encode(x, s, nr, seed=6, worker=w, bucket=512)
+            norms.append(nr)
+            codes.append(c)
+            sgns.append(sg)
+            dec.append(oracle.dither_decode(nr, c, sg, d, s, bucket=512))
+        sg_arr = np.stack(sgns) if sgns[0].size else None
+        o64, o32, oa = oracle.aggregate_dither(np.stack(norms), np.stack(codes), sg_arr, d, s, bucket=512)
+        dec = np.stack(dec)
+        ref = dec.astype(np.float64).sum(axis=0)
+        assert np.all(np.abs(o64 - ref) <= 1e-15 * np.abs(dec.astype(np.float64)).sum(axis=0))
+        seq = dec[0].copy()
+        for w in range(1, n):
+            seq = (seq + dec[w]).astype(np.float32)
+        assert np.array_equal(o32, seq)
