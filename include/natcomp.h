@@ -1,0 +1,163 @@
+/*
+ * natcomp.h -- C ABI of libnatcomp: natural compression C_nat and natural dithering
+ * D_nat^{p,s} of fp32 gradient vectors on one MI355X (gfx950), after
+ * "Natural Compression for Distributed Deep Learning" (arXiv 1905.10988).
+ *
+ * Conventions that hold for every entry point unless its comment says otherwise:
+ *   - Pointers marked DEVICE point to HIP device memory owned by the caller; the
+ *     library never allocates, frees or keeps them.  Pointers marked HOST are read
+ *     during the call only.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     enqueue their kernels on it and return without waiting.
+ *   - The return value reports argument errors (nothing was enqueued) and launch
+ *     failures.  No exception crosses this boundary.  d = 0 is accepted and does nothing.
+ *   - Inputs are never modified; an output may not overlap an input or another output.
+ *   - Randomness: element i of a call uses the 32-bit word of global index
+ *     g = index_offset + i of the stream (seed, worker, operator): output word (g mod 4)
+ *     of Philox-4x32-10 with key = (lo32(seed), hi32(seed)) and counter =
+ *     (lo32(g/4), hi32(g/4), worker, domain), domain 0 for C_nat and 1 for D_nat.
+ *     Results therefore do not depend on how a vector is split into calls or launches.
+ *
+ * Plane layouts (little-endian bit order inside a byte):
+ *   sign plane      bit (i mod 8) of byte i/8 is the sign bit of element i; ceil(d/8) bytes,
+ *                   unused high bits of the last byte are written as zero.
+ *   exponent plane  byte i is the 8-bit exponent field of C_nat(x_i); d bytes.
+ *   level codes     c = 0 is the level 0 and c in 1..s is the level 2^(c-s).  With
+ *                   b = ceil(log2(s+1)) bits per code:
+ *                     b <= 3: fused nibbles (sign << 3) | c, element i in byte i/2, low nibble
+ *                             for even i; no sign plane;
+ *                     b == 4: nibble plane of codes (same order) + sign plane;
+ *                     b >= 5: one byte per code + sign plane.
+ *                   Planes are indexed by the element's position in the call's vector.
+ */
+#ifndef NATCOMP_H
+#define NATCOMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    NC_OK = 0,
+    NC_ERR_NULL = 1,        /* a required pointer is NULL */
+    NC_ERR_INVALID = 2,     /* n = 0, s outside 1..127, bad strides or segment description */
+    NC_ERR_UNSUPPORTED = 3, /* p is not 1, 2 or INFINITY */
+    NC_ERR_WORKSPACE = 4,   /* workspace missing or too small */
+    NC_ERR_LAUNCH = 5       /* the HIP runtime refused a launch */
+} nc_status;
+
+/* Human-readable name of a status code (static storage). */
+const char *nc_status_string(nc_status st);
+
+/* ----------------------------------------------------------------------------------------
+ * Sizes (pure host functions).
+ * -------------------------------------------------------------------------------------- */
+size_t nc_nat_exp_bytes(uint64_t d);                   /* d */
+size_t nc_sign_bytes(uint64_t d);                      /* ceil(d/8) */
+size_t nc_dither_code_bytes(uint64_t d, uint32_t s);   /* ceil(d/2) for s <= 15, else d; 0 if s is invalid */
+size_t nc_dither_sign_bytes(uint64_t d, uint32_t s);   /* 0 for s <= 7, else ceil(d/8) */
+/* Suggested distance between the planes of consecutive workers: bytes rounded up to 256. */
+size_t nc_plane_stride(size_t bytes);
+/* Number of segments a description yields (see nc_dither_encode). */
+uint64_t nc_segment_count(uint64_t d, uint32_t num_segments, uint32_t bucket, int have_offsets);
+/* Bytes of DEVICE scratch nc_dither_encode needs for this description (0 when none). */
+size_t nc_dither_workspace_bytes(uint64_t d, uint32_t num_segments, uint32_t bucket, int have_offsets);
+
+/* ----------------------------------------------------------------------------------------
+ * Natural compression (Sec. 2, Def. 1; binary32 realisation in "From 32 to 9 bits").
+ *
+ * Each x_i = (-1)^sign 2^(e-127) (1+m) is rounded to 2^(e+1-127) with probability m and to
+ * 2^(e-127) otherwise, by comparing the random word r with the mantissa: up iff
+ * r < m * 2^32 (m as a fraction), an integer comparison on the bit pattern; no
+ * floating-point operation touches the value.  Zeros and exact powers of two are
+ * unchanged; subnormals go to 0 or 2^-126; exponent 255 (Inf, NaN) stays 255 and values
+ * in (2^127, 2^128) may round to it.  Output: exponent plane + sign plane.
+ *
+ *   x         DEVICE, d floats.
+ *   exp_out   DEVICE, nc_nat_exp_bytes(d) bytes.     sign_out  DEVICE, nc_sign_bytes(d) bytes.
+ * Fastest when x is 16-byte aligned, exp_out 8-byte aligned and index_offset a multiple
+ * of 4; any alignment and offset is accepted.
+ * -------------------------------------------------------------------------------------- */
+nc_status nc_nat_encode(const float *x, uint64_t d, uint64_t seed, uint32_t worker,
+                        uint64_t index_offset, uint8_t *exp_out, uint8_t *sign_out, void *stream);
+
+/* The same for n workers in one launch: worker w (stream id first_worker + w) reads
+ * x + w*x_stride (stride in floats) and writes exp_out + w*exp_stride and
+ * sign_out + w*sign_stride (strides in bytes).  Equal to n calls of nc_nat_encode. */
+nc_status nc_nat_encode_batch(const float *x, size_t x_stride, uint32_t n, uint64_t d, uint64_t seed,
+                              uint32_t first_worker, uint64_t index_offset, uint8_t *exp_out,
+                              size_t exp_stride, uint8_t *sign_out, size_t sign_stride, void *stream);
+
+/* Decoder: out_i has the stored sign and exponent and a zero mantissa ("computation-free",
+ * Sec. 2).  exp, sign DEVICE planes of d elements; out DEVICE, d floats. */
+nc_status nc_nat_decode(const uint8_t *exp, const uint8_t *sign, uint64_t d, float *out, void *stream);
+
+/* ----------------------------------------------------------------------------------------
+ * Natural dithering D_nat^{p,s} (Sec. 3, Def. 3 with levels 0, 2^(1-s), ..., 1/2, 1 and the
+ * norm sent uncompressed).
+ *
+ * The vector is cut into segments and each is normalised by its own p-norm (the paper
+ * normalises the whole vector: that is the single-segment case).  Segments are given by
+ *   seg_offsets != NULL: DEVICE array of num_segments+1 ascending uint64, first 0, last d
+ *                        (empty segments allowed); bucket ignored;
+ *   seg_offsets == NULL, bucket > 0: consecutive buckets of `bucket` elements (last shorter);
+ *   seg_offsets == NULL, bucket == 0: one segment.
+ * Per element: y = fl(|x_i| * fl(1/norm)) in binary32; y between adjacent levels
+ * l_low <= y <= l_high goes to l_high with probability (y - l_low)/(l_high - l_low), decided
+ * by an integer comparison of the random word with a threshold built from y's bits; y >= 1
+ * is the level 1.  A segment whose norm is below 2^-126 (zero included) codes to zeros.
+ *
+ *   p           1, 2 or INFINITY.               s  number of levels, 1..127.
+ *   norms_out   DEVICE, one float per segment: the p-norm (sum accumulated in double,
+ *               rounded once to binary32; the maximum for p = INFINITY is exact).
+ *   code_out    DEVICE, nc_dither_code_bytes(d, s).
+ *   sign_out    DEVICE, nc_dither_sign_bytes(d, s); may be NULL when that is 0.
+ *   workspace   DEVICE scratch of at least nc_dither_workspace_bytes(...) bytes, 8-byte
+ *               aligned; may be NULL when that is 0.  Contents need not be initialised.
+ * -------------------------------------------------------------------------------------- */
+nc_status nc_dither_encode(const float *x, uint64_t d, const uint64_t *seg_offsets, uint32_t num_segments,
+                           uint32_t bucket, float p, uint32_t s, uint64_t seed, uint32_t worker,
+                           uint64_t index_offset, float *norms_out, uint8_t *code_out, uint8_t *sign_out,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* Decoder: out_i = sign * fl(norm_segment * 2^(c-s)), a signed zero for c = 0 (multiplying by
+ * the level is an exponent addition, Sec. 3 and the fast-aggregation remark). */
+nc_status nc_dither_decode(const float *norms, const uint8_t *code, const uint8_t *sign, uint64_t d,
+                           const uint64_t *seg_offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
+                           float *out, void *stream);
+
+/* ----------------------------------------------------------------------------------------
+ * Master-side aggregation (Algorithm 1: Delta = sum over workers of the decompressed
+ * updates).  One fused kernel decodes the n code streams and adds them in binary32 in the
+ * fixed order ((v_0 + v_1) + v_2) + ... ; the result is the sum, not the mean.
+ *
+ * The descriptor is a HOST struct.  Worker w's planes start at code + w*code_stride,
+ * sign + w*sign_stride (bytes) and norms + w*norm_stride (floats).
+ *   kind = NC_KIND_NAT:    code is the exponent plane; norms, s and the segment fields unused.
+ *   kind = NC_KIND_DITHER: code/sign/norms as written by nc_dither_encode with the same s and
+ *                          segment description; sign may be NULL when s <= 7.
+ * out: DEVICE, d floats.  Fastest when strides are multiples of 16 and planes 16-byte aligned.
+ * -------------------------------------------------------------------------------------- */
+enum { NC_KIND_NAT = 0, NC_KIND_DITHER = 1 };
+
+typedef struct {
+    int32_t kind;
+    uint32_t n;                 /* number of workers, >= 1 */
+    uint64_t d;
+    uint32_t s;                 /* D_nat only */
+    uint32_t bucket;            /* D_nat only */
+    const uint8_t *code;   size_t code_stride;
+    const uint8_t *sign;   size_t sign_stride;
+    const float *norms;    size_t norm_stride;      /* D_nat only */
+    const uint64_t *seg_offsets; uint32_t num_segments; uint32_t reserved; /* D_nat only */
+} nc_agg_desc;
+
+nc_status nc_aggregate_sum(const nc_agg_desc *desc, float *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NATCOMP_H */

@@ -1,0 +1,114 @@
+// C ABI of libnatcomp: argument validation, alignment-based path selection and kernel
+// launches.  Declarations and the meaning of every argument are in include/natcomp.h.
+#include "../../include/natcomp.h"
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+
+#include "kernels.hpp"
+
+using namespace natcomp;
+
+namespace {
+
+constexpr uint64_t kMaxD = 1ull << 40;  // keeps every grid dimension below 2^31
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline nc_status from_hip(hipError_t e) { return e == hipSuccess ? NC_OK : NC_ERR_LAUNCH; }
+inline uint32_t code_width(uint32_t s) { uint32_t b = 0; while ((1u << b) < s + 1) ++b; return b; }
+inline bool valid_s(uint32_t s) { return s >= 1 && s <= 127; }
+
+}  // namespace
+
+extern "C" {
+
+const char* nc_status_string(nc_status st) {
+    switch (st) {
+        case NC_OK: return "NC_OK";
+        case NC_ERR_NULL: return "NC_ERR_NULL";
+        case NC_ERR_INVALID: return "NC_ERR_INVALID";
+        case NC_ERR_UNSUPPORTED: return "NC_ERR_UNSUPPORTED";
+        case NC_ERR_WORKSPACE: return "NC_ERR_WORKSPACE";
+        case NC_ERR_LAUNCH: return "NC_ERR_LAUNCH";
+    }
+    return "NC_ERR_?";
+}
+
+size_t nc_nat_exp_bytes(uint64_t d) { return (size_t)d; }
+size_t nc_sign_bytes(uint64_t d) { return (size_t)((d + 7) / 8); }
+size_t nc_dither_code_bytes(uint64_t d, uint32_t s) {
+    if (!valid_s(s)) return 0;
+    return code_width(s) <= 4 ? (size_t)((d + 1) / 2) : (size_t)d;
+}
+size_t nc_dither_sign_bytes(uint64_t d, uint32_t s) {
+    if (!valid_s(s)) return 0;
+    return code_width(s) <= 3 ? 0 : (size_t)((d + 7) / 8);
+}
+size_t nc_plane_stride(size_t bytes) { return (bytes + 255) & ~(size_t)255; }
+
+uint64_t nc_segment_count(uint64_t d, uint32_t num_segments, uint32_t bucket, int have_offsets) {
+    if (have_offsets) return num_segments;
+    if (bucket) return (d + bucket - 1) / bucket;
+    return 1;
+}
+
+nc_status nc_nat_encode_batch(const float* x, size_t x_stride, uint32_t n, uint64_t d, uint64_t seed,
+                              uint32_t first_worker, uint64_t index_offset, uint8_t* exp_out, size_t exp_stride,
+                              uint8_t* sign_out, size_t sign_stride, void* stream) {
+    if (n == 0 || d > kMaxD || n > 65535) return NC_ERR_INVALID;
+    if (d == 0) return NC_OK;
+    if (!x || !exp_out || !sign_out) return NC_ERR_NULL;
+    if (n > 1 && (x_stride < d || exp_stride < nc_nat_exp_bytes(d) || sign_stride < nc_sign_bytes(d)))
+        return NC_ERR_INVALID;
+    NatEncodeArgs a;
+    a.x = x; a.x_stride = x_stride; a.d = d;
+    a.k0 = (uint32_t)seed; a.k1 = (uint32_t)(seed >> 32);
+    a.first_worker = first_worker; a.index_offset = index_offset;
+    a.exp_out = exp_out; a.exp_stride = exp_stride; a.sign_out = sign_out; a.sign_stride = sign_stride;
+    const bool fast = aligned(x, 16) && aligned(exp_out, 8) && (index_offset & 3) == 0 &&
+                      (n == 1 || ((x_stride & 3) == 0 && (exp_stride & 7) == 0));
+    return from_hip(launch_nat_encode(a, n, fast, (hipStream_t)stream));
+}
+
+nc_status nc_nat_encode(const float* x, uint64_t d, uint64_t seed, uint32_t worker, uint64_t index_offset,
+                        uint8_t* exp_out, uint8_t* sign_out, void* stream) {
+    return nc_nat_encode_batch(x, 0, 1, d, seed, worker, index_offset, exp_out, 0, sign_out, 0, stream);
+}
+
+nc_status nc_nat_decode(const uint8_t* exp, const uint8_t* sign, uint64_t d, float* out, void* stream) {
+    if (d > kMaxD) return NC_ERR_INVALID;
+    if (d == 0) return NC_OK;
+    if (!exp || !sign || !out) return NC_ERR_NULL;
+    NatDecodeArgs a{exp, sign, d, out};
+    const bool fast = aligned(exp, 8) && aligned(out, 16);
+    return from_hip(launch_nat_decode(a, fast, (hipStream_t)stream));
+}
+
+nc_status nc_dither_encode(const float*, uint64_t, const uint64_t*, uint32_t, uint32_t, float, uint32_t, uint64_t,
+                           uint32_t, uint64_t, float*, uint8_t*, uint8_t*, void*, size_t, void*) {
+    return NC_ERR_UNSUPPORTED;
+}
+nc_status nc_dither_decode(const float*, const uint8_t*, const uint8_t*, uint64_t, const uint64_t*, uint32_t,
+                           uint32_t, uint32_t, float*, void*) {
+    return NC_ERR_UNSUPPORTED;
+}
+size_t nc_dither_workspace_bytes(uint64_t, uint32_t, uint32_t, int) { return 0; }
+
+nc_status nc_aggregate_sum(const nc_agg_desc* desc, float* out, void* stream) {
+    if (!desc) return NC_ERR_NULL;
+    if (desc->n == 0 || desc->d > kMaxD) return NC_ERR_INVALID;
+    if (desc->kind != NC_KIND_NAT && desc->kind != NC_KIND_DITHER) return NC_ERR_INVALID;
+    if (desc->d == 0) return NC_OK;
+    if (!out || !desc->code) return NC_ERR_NULL;
+    if (desc->kind == NC_KIND_NAT) {
+        if (!desc->sign) return NC_ERR_NULL;
+        if (desc->n > 1 && (desc->code_stride < nc_nat_exp_bytes(desc->d) || desc->sign_stride < nc_sign_bytes(desc->d)))
+            return NC_ERR_INVALID;
+        NatAggregateArgs a{desc->code, desc->code_stride, desc->sign, desc->sign_stride, desc->n, desc->d, out};
+        const bool fast = aligned(desc->code, 8) && aligned(out, 16) && (desc->n == 1 || (desc->code_stride & 7) == 0);
+        return from_hip(launch_nat_aggregate(a, fast, (hipStream_t)stream));
+    }
+    return NC_ERR_UNSUPPORTED;
+}
+
+}  // extern "C"

@@ -1,0 +1,256 @@
+"""ctypes binding of libnatcomp's C ABI (include/natcomp.h).
+
+Argument marshalling only: every function checks tensor device/dtype/contiguity, passes
+raw device pointers, sizes and the current HIP stream to the entry point of the same
+name, and raises on a non-zero status.  PyTorch is used for device memory and streams
+and for nothing else.  There is no fallback: if libnatcomp.so has not been built the
+first call raises.
+"""
+import ctypes
+import math
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnatcomp.so")
+
+NC_KIND_NAT = 0
+NC_KIND_DITHER = 1
+
+_vp, _u32, _u64, _sz = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_size_t
+
+
+class AggDesc(ctypes.Structure):
+    """Mirror of nc_agg_desc."""
+    _fields_ = [
+        ("kind", ctypes.c_int32), ("n", _u32), ("d", _u64), ("s", _u32), ("bucket", _u32),
+        ("code", _vp), ("code_stride", _sz),
+        ("sign", _vp), ("sign_stride", _sz),
+        ("norms", _vp), ("norm_stride", _sz),
+        ("seg_offsets", _vp), ("num_segments", _u32), ("reserved", _u32),
+    ]
+
+
+class NatcompError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise NatcompError(f"{LIB_PATH} is missing: run `python -m paper_1905_10988_amd.build` first")
+        L = ctypes.CDLL(LIB_PATH)
+        L.nc_status_string.argtypes = [ctypes.c_int]
+        L.nc_status_string.restype = ctypes.c_char_p
+        for name, args in {
+            "nc_nat_exp_bytes": [_u64], "nc_sign_bytes": [_u64],
+            "nc_dither_code_bytes": [_u64, _u32], "nc_dither_sign_bytes": [_u64, _u32],
+            "nc_plane_stride": [_sz],
+            "nc_dither_workspace_bytes": [_u64, _u32, _u32, ctypes.c_int],
+        }.items():
+            getattr(L, name).argtypes = args
+            getattr(L, name).restype = _sz
+        L.nc_segment_count.argtypes = [_u64, _u32, _u32, ctypes.c_int]
+        L.nc_segment_count.restype = _u64
+        L.nc_nat_encode.argtypes = [_vp, _u64, _u64, _u32, _u64, _vp, _vp, _vp]
+        L.nc_nat_encode_batch.argtypes = [_vp, _sz, _u32, _u64, _u64, _u32, _u64, _vp, _sz, _vp, _sz, _vp]
+        L.nc_nat_decode.argtypes = [_vp, _vp, _u64, _vp, _vp]
+        L.nc_dither_encode.argtypes = [_vp, _u64, _vp, _u32, _u32, ctypes.c_float, _u32, _u64, _u32, _u64,
+                                       _vp, _vp, _vp, _vp, _sz, _vp]
+        L.nc_dither_decode.argtypes = [_vp, _vp, _vp, _u64, _vp, _u32, _u32, _u32, _vp, _vp]
+        L.nc_aggregate_sum.argtypes = [ctypes.POINTER(AggDesc), _vp, _vp]
+        for name in ("nc_nat_encode", "nc_nat_encode_batch", "nc_nat_decode", "nc_dither_encode",
+                     "nc_dither_decode", "nc_aggregate_sum"):
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != 0:
+        raise NatcompError(lib().nc_status_string(status).decode())
+
+
+def _stream():
+    return _vp(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, name):
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: expected a contiguous {dtype} tensor on the GPU")
+    return t
+
+
+def _ptr(t):
+    return _vp(0 if t is None else t.data_ptr())
+
+
+# ------------------------------------------------------------------ sizes
+def nat_exp_bytes(d):
+    return lib().nc_nat_exp_bytes(d)
+
+
+def sign_bytes(d):
+    return lib().nc_sign_bytes(d)
+
+
+def dither_code_bytes(d, s):
+    return lib().nc_dither_code_bytes(d, s)
+
+
+def dither_sign_bytes(d, s):
+    return lib().nc_dither_sign_bytes(d, s)
+
+
+def plane_stride(nbytes):
+    return lib().nc_plane_stride(nbytes)
+
+
+def segment_count(d, num_segments=0, bucket=0, have_offsets=False):
+    return lib().nc_segment_count(d, num_segments, bucket, int(have_offsets))
+
+
+def dither_workspace_bytes(d, num_segments=0, bucket=0, have_offsets=False):
+    return lib().nc_dither_workspace_bytes(d, num_segments, bucket, int(have_offsets))
+
+
+# ------------------------------------------------------------------ natural compression
+def nat_encode(x, seed, worker=0, index_offset=0, exp_out=None, sign_out=None):
+    """nc_nat_encode: returns (exponent plane, sign plane) as uint8 tensors."""
+    x = _dev(x, torch.float32, "x")
+    d = x.numel()
+    if exp_out is None:
+        exp_out = torch.empty(nat_exp_bytes(d), dtype=torch.uint8, device=x.device)
+    if sign_out is None:
+        sign_out = torch.empty(sign_bytes(d), dtype=torch.uint8, device=x.device)
+    _dev(exp_out, torch.uint8, "exp_out")
+    _dev(sign_out, torch.uint8, "sign_out")
+    assert exp_out.numel() >= nat_exp_bytes(d) and sign_out.numel() >= sign_bytes(d)
+    _check(lib().nc_nat_encode(_ptr(x), d, seed, worker, index_offset, _ptr(exp_out), _ptr(sign_out), _stream()))
+    return exp_out, sign_out
+
+
+def nat_encode_batch(x, seed, first_worker=0, index_offset=0, exp_out=None, sign_out=None, d=None):
+    """nc_nat_encode_batch: x is (n, row) float32 with the first d entries of each row used;
+    outputs are (n, exp_stride) and (n, sign_stride) uint8 with 256-byte-multiple strides."""
+    x = _dev(x, torch.float32, "x")
+    assert x.dim() == 2
+    n, row = x.shape
+    d = row if d is None else d
+    assert d <= row
+    if exp_out is None:
+        exp_out = torch.empty((n, plane_stride(nat_exp_bytes(d))), dtype=torch.uint8, device=x.device)
+    if sign_out is None:
+        sign_out = torch.empty((n, plane_stride(sign_bytes(d))), dtype=torch.uint8, device=x.device)
+    _dev(exp_out, torch.uint8, "exp_out")
+    _dev(sign_out, torch.uint8, "sign_out")
+    assert exp_out.shape[0] == n and sign_out.shape[0] == n
+    assert exp_out.shape[1] >= nat_exp_bytes(d) and sign_out.shape[1] >= sign_bytes(d)
+    _check(lib().nc_nat_encode_batch(_ptr(x), row, n, d, seed, first_worker, index_offset, _ptr(exp_out),
+                                     exp_out.shape[1], _ptr(sign_out), sign_out.shape[1], _stream()))
+    return exp_out, sign_out
+
+
+def nat_decode(exp, sign, d, out=None):
+    """nc_nat_decode."""
+    exp = _dev(exp, torch.uint8, "exp")
+    sign = _dev(sign, torch.uint8, "sign")
+    assert exp.numel() >= nat_exp_bytes(d) and sign.numel() >= sign_bytes(d)
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=exp.device)
+    _dev(out, torch.float32, "out")
+    assert out.numel() >= d
+    _check(lib().nc_nat_decode(_ptr(exp), _ptr(sign), d, _ptr(out), _stream()))
+    return out
+
+
+# ------------------------------------------------------------------ natural dithering
+def _segments(d, seg_offsets, bucket):
+    if seg_offsets is not None:
+        seg_offsets = _dev(seg_offsets, torch.int64, "seg_offsets")   # uint64 values held in an int64 tensor
+        return seg_offsets, seg_offsets.numel() - 1, 0, seg_offsets.numel() - 1
+    bucket = int(bucket or 0)
+    return None, 0, bucket, segment_count(d, 0, bucket, False)
+
+
+def dither_encode(x, p, s, seed, worker=0, index_offset=0, seg_offsets=None, bucket=0,
+                  norms_out=None, code_out=None, sign_out=None, workspace=None):
+    """nc_dither_encode: returns (norms, code plane, sign plane or None)."""
+    x = _dev(x, torch.float32, "x")
+    d = x.numel()
+    off, nseg, bucket, count = _segments(d, seg_offsets, bucket)
+    if norms_out is None:
+        norms_out = torch.empty(count, dtype=torch.float32, device=x.device)
+    if code_out is None:
+        code_out = torch.empty(dither_code_bytes(d, s), dtype=torch.uint8, device=x.device)
+    nsign = dither_sign_bytes(d, s)
+    if sign_out is None and nsign:
+        sign_out = torch.empty(nsign, dtype=torch.uint8, device=x.device)
+    need = dither_workspace_bytes(d, nseg, bucket, off is not None)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    _dev(norms_out, torch.float32, "norms_out")
+    _dev(code_out, torch.uint8, "code_out")
+    _dev(sign_out, torch.uint8, "sign_out")
+    _dev(workspace, torch.uint8, "workspace")
+    assert norms_out.numel() >= count
+    _check(lib().nc_dither_encode(_ptr(x), d, _ptr(off), nseg, bucket, float(p), s, seed, worker, index_offset,
+                                  _ptr(norms_out), _ptr(code_out), _ptr(sign_out), _ptr(workspace),
+                                  0 if workspace is None else workspace.numel(), _stream()))
+    return norms_out, code_out, sign_out
+
+
+def dither_decode(norms, code, sign, d, s, seg_offsets=None, bucket=0, out=None):
+    """nc_dither_decode."""
+    norms = _dev(norms, torch.float32, "norms")
+    code = _dev(code, torch.uint8, "code")
+    sign = _dev(sign, torch.uint8, "sign")
+    off, nseg, bucket, count = _segments(d, seg_offsets, bucket)
+    assert norms.numel() >= count
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=code.device)
+    _dev(out, torch.float32, "out")
+    _check(lib().nc_dither_decode(_ptr(norms), _ptr(code), _ptr(sign), d, _ptr(off), nseg, bucket, s, _ptr(out),
+                                  _stream()))
+    return out
+
+
+# ------------------------------------------------------------------ sum over workers
+def aggregate_sum(kind, d, code, sign=None, norms=None, s=0, seg_offsets=None, bucket=0, out=None):
+    """nc_aggregate_sum over the rows of 2-D plane tensors (row w = worker w)."""
+    code = _dev(code, torch.uint8, "code")
+    sign = _dev(sign, torch.uint8, "sign")
+    norms = _dev(norms, torch.float32, "norms")
+    assert code.dim() == 2
+    n = code.shape[0]
+    desc = AggDesc()
+    desc.kind, desc.n, desc.d, desc.s = kind, n, d, s
+    desc.code, desc.code_stride = code.data_ptr(), code.shape[1]
+    if sign is not None:
+        assert sign.dim() == 2 and sign.shape[0] == n
+        desc.sign, desc.sign_stride = sign.data_ptr(), sign.shape[1]
+    if kind == NC_KIND_DITHER:
+        off, nseg, bucket, count = _segments(d, seg_offsets, bucket)
+        assert norms is not None and norms.dim() == 2 and norms.shape[0] == n and norms.shape[1] >= count
+        desc.norms, desc.norm_stride = norms.data_ptr(), norms.shape[1]
+        desc.seg_offsets = 0 if off is None else off.data_ptr()
+        desc.num_segments, desc.bucket = nseg, bucket
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=code.device)
+    _dev(out, torch.float32, "out")
+    assert out.numel() >= d
+    _check(lib().nc_aggregate_sum(ctypes.byref(desc), _ptr(out), _stream()))
+    return out
+
+
+def p_value(p):
+    """The float the ABI expects for p (math.inf for the max-norm)."""
+    return math.inf if p in ("inf", math.inf) else float(p)

@@ -1,0 +1,74 @@
+"""The C-ABI shared library loads and exports every symbol include/natcomp.h declares (no GPU
+compute), and its host-side size functions and argument checks behave as documented."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def nc():
+    from paper_1905_10988_amd import natcomp
+    if not os.path.exists(natcomp.LIB_PATH):
+        from paper_1905_10988_amd import build
+        build.build(force=True)
+    return natcomp
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "natcomp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(nc):
+    names = declared_symbols()
+    assert {"nc_nat_encode", "nc_nat_decode", "nc_dither_encode", "nc_dither_decode", "nc_aggregate_sum"} <= set(names)
+    L = ctypes.CDLL(nc.LIB_PATH)
+    for name in names:
+        assert hasattr(L, name), name
+
+
+def test_size_functions(nc):
+    assert nc.nat_exp_bytes(0) == 0 and nc.nat_exp_bytes(1000) == 1000
+    assert [nc.sign_bytes(d) for d in (0, 1, 8, 9, 25_557_032)] == [0, 1, 1, 2, 3_194_629]
+    assert nc.dither_code_bytes(9, 4) == 5 and nc.dither_sign_bytes(9, 4) == 0       # fused nibbles
+    assert nc.dither_code_bytes(9, 7) == 5 and nc.dither_sign_bytes(9, 7) == 0
+    assert nc.dither_code_bytes(9, 8) == 5 and nc.dither_sign_bytes(9, 8) == 2       # nibble + sign plane
+    assert nc.dither_code_bytes(9, 15) == 5 and nc.dither_code_bytes(9, 16) == 9     # byte codes from s = 16
+    assert nc.dither_code_bytes(9, 0) == 0 and nc.dither_code_bytes(9, 128) == 0     # invalid s
+    assert nc.plane_stride(1) == 256 and nc.plane_stride(256) == 256 and nc.plane_stride(257) == 512
+    assert nc.segment_count(100, 0, 0, False) == 1
+    assert nc.segment_count(100, 0, 8, False) == 13
+    assert nc.segment_count(100, 7, 8, True) == 7
+
+
+def test_sizes_agree_with_oracle_layout(nc, oracle):
+    for d in (0, 1, 2, 7, 8, 9, 1001):
+        for s in (1, 3, 4, 7, 8, 15, 16, 127):
+            assert nc.dither_code_bytes(d, s) == oracle.dither_code_bytes(d, s)
+            assert nc.dither_sign_bytes(d, s) == oracle.dither_sign_bytes(d, s)
+
+
+def test_argument_errors_without_touching_the_gpu(nc):
+    L = nc.lib()
+    one = ctypes.c_void_p(256)      # never dereferenced: the checks below fail before any launch
+    # NULL pointers
+    assert L.nc_nat_encode(None, 8, 0, 0, 0, one, one, None) == 1
+    assert L.nc_nat_decode(one, None, 8, one, None) == 1
+    assert L.nc_aggregate_sum(None, one, None) == 1
+    # d = 0 is a no-op
+    assert L.nc_nat_encode(None, 0, 0, 0, 0, None, None, None) == 0
+    assert L.nc_nat_decode(None, None, 0, None, None) == 0
+    # n = 0, strides shorter than a plane, unknown kind
+    assert L.nc_nat_encode_batch(one, 8, 0, 8, 0, 0, 0, one, 8, one, 1, None) == 2
+    assert L.nc_nat_encode_batch(one, 4, 2, 8, 0, 0, 0, one, 8, one, 1, None) == 2
+    desc = nc.AggDesc()
+    desc.kind, desc.n, desc.d = 7, 1, 8
+    assert L.nc_aggregate_sum(ctypes.byref(desc), one, None) == 2
+    desc.kind, desc.n = nc.NC_KIND_NAT, 0
+    assert L.nc_aggregate_sum(ctypes.byref(desc), one, None) == 2
+    assert L.nc_status_string(0) == b"NC_OK" and L.nc_status_string(3) == b"NC_ERR_UNSUPPORTED"

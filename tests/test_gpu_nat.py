@@ -1,0 +1,199 @@
+"""GPU parity of natural compression: the HIP library (through its C ABI) against the CPU
+oracle, element by element on the same seeded inputs.  Codes and decoded values must be
+bit-exact; the n-way binary32 sum must equal the oracle's left-to-right binary32 sum and lie
+within 1e-5 * sum|v| of its double sum."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import Guarded, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def nc():
+    from paper_1905_10988_amd import natcomp
+    natcomp.lib()
+    assert torch.cuda.is_available()
+    return natcomp
+
+
+@pytest.fixture(scope="module")
+def wl():
+    from paper_1905_10988_amd import workloads
+    return workloads
+
+
+def encode_checked(nc, oracle, x, seed, worker=0, index_offset=0, xdev=None):
+    d = x.size
+    xdev = dev(x) if xdev is None else xdev
+    e_buf, s_buf = Guarded(nc.nat_exp_bytes(d)), Guarded(nc.sign_bytes(d))
+    nc.nat_encode(xdev, seed, worker, index_offset, exp_out=e_buf.t, sign_out=s_buf.t)
+    torch.cuda.synchronize()
+    e, s = e_buf.check(), s_buf.check()
+    eo, so = oracle.nat_encode(x, seed, worker, index_offset)
+    assert np.array_equal(e, eo), f"exponent plane differs at {np.flatnonzero(e != eo)[:8]}"
+    assert np.array_equal(s, so), f"sign plane differs at {np.flatnonzero(s != so)[:8]}"
+    return e_buf.t, s_buf.t, eo, so
+
+
+def test_config1_encode_decode(nc, oracle, wl):
+    """Config 1: d = 2^20, N(0,1)*1e-3 with 1 % exact powers of two and 0.1 % zeros, seed 0."""
+    x = wl.config1()
+    d = x.size
+    e_t, s_t, eo, so = encode_checked(nc, oracle, x, seed=0)
+    out = Guarded(d, torch.float32)
+    nc.nat_decode(e_t, s_t, d, out=out.t)
+    torch.cuda.synchronize()
+    y = out.check()
+    yo = oracle.nat_decode(eo, so, d)
+    assert np.array_equal(y.view(np.uint32), yo.view(np.uint32))
+    # the pass-through invariants hold on the GPU result itself
+    ax = np.abs(x)
+    pow2 = (ax > 0) & (np.frexp(ax)[0] == 0.5)
+    assert pow2.sum() > 10000 and np.array_equal(y[pow2], x[pow2])
+    zero = x == 0
+    assert zero.sum() > 1000 and np.array_equal(y[zero].view(np.uint32), x[zero].view(np.uint32))
+    # run-to-run determinism
+    e2, s2 = nc.nat_encode(dev(x), 0)
+    assert torch.equal(e2, e_t) and torch.equal(s2, s_t)
+
+
+@pytest.mark.parametrize("d", [1, 7, 8, 9, 63, 64, 65, 2047, 2048, 2049, 100003])
+def test_ragged_sizes(nc, oracle, wl, d):
+    x = wl.config1(d=max(d, 2000), seed=d)[:d].copy()
+    e_t, s_t, eo, so = encode_checked(nc, oracle, x, seed=3, worker=5)
+    out = Guarded(d, torch.float32)
+    nc.nat_decode(e_t, s_t, d, out=out.t)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.check().view(np.uint32), oracle.nat_decode(eo, so, d).view(np.uint32))
+
+
+@pytest.mark.parametrize("shift,index_offset", [(0, 4), (0, 1), (0, 6), (1, 0), (3, 8), (2, 2**34 + 4), (0, 2**36), (1, 2**33 + 3)])
+def test_unaligned_and_offsets(nc, oracle, wl, shift, index_offset):
+    """Any pointer alignment and any index offset give the oracle's codes (slow path), and a
+    slice encoded with its offset equals the same slice of the whole vector."""
+    d = 10007
+    base = wl.config1(d=d + 8, seed=17)
+    x = base[shift: shift + d].copy()
+    xdev = dev(base)[shift: shift + d]
+    encode_checked(nc, oracle, x, seed=11, worker=1, index_offset=index_offset, xdev=xdev)
+
+
+def test_slices_match_whole_vector(nc, oracle, wl):
+    x = wl.config1(d=50000, seed=5)
+    xdev = dev(x)
+    e_all, s_all = nc.nat_encode(xdev, 9, worker=2)
+    full = host(nc.nat_decode(e_all, s_all, x.size))
+    for a, b in [(0, 4096), (4096, 50000), (13, 777), (40001, 49999)]:
+        e, s = nc.nat_encode(xdev[a:b], 9, worker=2, index_offset=a)
+        part = host(nc.nat_decode(e, s, b - a))
+        assert np.array_equal(part.view(np.uint32), full[a:b].view(np.uint32))
+        assert torch.equal(e, e_all[a:b])
+
+
+def test_edge_values(nc, oracle, wl):
+    x = np.tile(wl.edge_values(), 41)
+    e_t, s_t, eo, so = encode_checked(nc, oracle, x, seed=2)
+    y = host(nc.nat_decode(e_t, s_t, x.size))
+    assert np.array_equal(y.view(np.uint32), oracle.nat_decode(eo, so, x.size).view(np.uint32))
+
+
+def test_empty_input(nc):
+    x = torch.empty(0, dtype=torch.float32, device="cuda")
+    e, s = nc.nat_encode(x, 1)
+    assert e.numel() == 0 and s.numel() == 0
+    assert nc.nat_decode(e, s, 0).numel() == 0
+
+
+def test_batch_equals_single_calls(nc, oracle, wl):
+    n, d = 5, 30011
+    off = wl.layer_offsets(d=d, num_layers=9, lo=64, hi=20000, seed=2)
+    rows = np.zeros((n, d + 5), np.float32)
+    for w in range(n):
+        rows[w, :d] = wl.layered_gaussian(w, off, seed=31)
+    xdev = dev(rows)
+    exp, sign = nc.nat_encode_batch(xdev, seed=77, first_worker=3, d=d)
+    torch.cuda.synchronize()
+    for w in range(n):
+        eo, so = oracle.nat_encode(rows[w, :d], 77, 3 + w)
+        assert np.array_equal(host(exp[w, :d]), eo)
+        assert np.array_equal(host(sign[w, : so.size]), so)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 8, 9, 16, 17])
+@pytest.mark.parametrize("d", [5, 4099, 65536])
+def test_aggregate_small(nc, oracle, wl, n, d):
+    off = wl.layer_offsets(d=d, num_layers=min(7, max(1, d // 64)), lo=min(64, d), hi=max(d, 64), seed=3) if d >= 64 \
+        else np.array([0, d], np.uint64)
+    x = np.stack([wl.layered_gaussian(w, off, seed=41) for w in range(n)])
+    exp, sign = nc.nat_encode_batch(dev(x), seed=5)
+    out = Guarded(d, torch.float32)
+    nc.aggregate_sum(nc.NC_KIND_NAT, d, exp, sign, out=out.t)
+    torch.cuda.synchronize()
+    got = out.check()
+    o64, o32, oa = oracle.aggregate_nat(host(exp), host(sign), d)
+    assert np.array_equal(got.view(np.uint32), o32.view(np.uint32))
+    assert np.all(np.abs(got.astype(np.float64) - o64) <= 1e-5 * oa)
+
+
+def test_aggregate_odd_strides_and_cancellation(nc, oracle):
+    """Strides that are not multiples of 8 (slow path), and +v / -v pairs that cancel to zero."""
+    d, n = 1003, 4
+    rng = np.random.default_rng(8)
+    base = (rng.standard_normal(d) * 1e-2).astype(np.float32)
+    x = np.stack([base, -base, base * 3, -base * 3]).astype(np.float32)
+    es, ss = d + 3, (d + 7) // 8 + 1
+    exp = torch.zeros((n, es), dtype=torch.uint8, device="cuda")
+    sign = torch.zeros((n, ss), dtype=torch.uint8, device="cuda")
+    xdev = dev(x)
+    for w in range(n):
+        nc.nat_encode(xdev[w], 4, worker=0, exp_out=exp[w, :d], sign_out=sign[w, : (d + 7) // 8])
+    got = host(nc.aggregate_sum(nc.NC_KIND_NAT, d, exp, sign))
+    o64, o32, oa = oracle.aggregate_nat(host(exp), host(sign), d)
+    assert np.array_equal(got.view(np.uint32), o32.view(np.uint32))
+    # same worker id and seed for x and -x: identical draws, exact cancellation in pairs 0/1
+    first_two = host(nc.aggregate_sum(nc.NC_KIND_NAT, d, exp[:2].contiguous(), sign[:2].contiguous()))
+    assert np.all(first_two == 0)
+
+
+def test_config2_full_size(nc, oracle, wl):
+    """Config 2 at its full size and in the launch shape the benchmark times: d = 25,557,032
+    in 161 layers, 8 workers encoded by one batched call, then the fused decode+sum.  Two
+    workers' planes are compared in full, the others and the sum on sampled windows."""
+    d, n = wl.D_RESNET50, wl.NUM_WORKERS
+    off = wl.layer_offsets()
+    row = (d + 63) // 64 * 64
+    xdev = torch.empty((n, row), dtype=torch.float32, device="cuda")
+    xs = []
+    for w in range(n):
+        xw = wl.layered_gaussian(w, off)
+        xs.append(xw)
+        xdev[w, :d] = torch.from_numpy(xw).cuda()
+    exp, sign = nc.nat_encode_batch(xdev, seed=0, d=d)
+    out = nc.aggregate_sum(nc.NC_KIND_NAT, d, exp, sign)
+    torch.cuda.synchronize()
+    nsb = nc.sign_bytes(d)
+    for w in (0, n - 1):
+        eo, so = oracle.nat_encode(xs[w], 0, w)
+        assert np.array_equal(host(exp[w, :d]), eo)
+        assert np.array_equal(host(sign[w, :nsb]), so)
+    rng = np.random.default_rng(1)
+    starts = [0, d - 4096 - (d % 8)] + (rng.integers(0, (d - 4096) // 8, 6) * 8).tolist()
+    got = host(out)
+    for a in starts:
+        b = min(a + 4096, d)
+        ew = np.stack([oracle.nat_encode(xs[w][a:b], 0, w, index_offset=a)[0] for w in range(n)])
+        sw = np.stack([oracle.nat_encode(xs[w][a:b], 0, w, index_offset=a)[1] for w in range(n)])
+        assert np.array_equal(host(exp[:, a:b]), ew)
+        assert np.array_equal(host(sign[:, a // 8: a // 8 + sw.shape[1]]), sw)
+        o64, o32, oa = oracle.aggregate_nat(ew, sw, b - a)
+        assert np.array_equal(got[a:b].view(np.uint32), o32.view(np.uint32))
+        assert np.all(np.abs(got[a:b].astype(np.float64) - o64) <= 1e-5 * oa)
+    # tail: the last partial group of 8 (d mod 8 = 0 here, so check the last 40 elements too)
+    a = d - 40
+    o64, o32, oa = oracle.aggregate_nat(
+        np.stack([oracle.nat_encode(xs[w][a:], 0, w, index_offset=a)[0] for w in range(n)]),
+        np.stack([oracle.nat_encode(xs[w][a:], 0, w, index_offset=a)[1] for w in range(n)]), 40)
+    assert np.array_equal(got[a:].view(np.uint32), o32.view(np.uint32))
