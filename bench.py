@@ -1,0 +1,188 @@
+"""Benchmark of the hot path on one MI355X.
+
+A step is one pass of config 2 (benchmark configs[1]): natural compression of 8 workers'
+gradients (d = 25,557,032 fp32 each, 161 layers) in one batched launch, then the fused
+decode-and-sum of the 8 code streams.  Inputs are resident in HBM before the timed region.
+`value` is fp32 input bytes (8 * 4 * d) per second of step time.
+
+Prints ONE JSON line with the metric, a `roofline` object for the dominant kernel (the
+batched encoder) and a `cpu_baseline` object (the CPU oracle timed on the host cores).
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+ENCODE_BYTES_PER_ELEM = 4 + 1 + 1 / 8            # read fp32, write exponent byte + sign bit
+
+
+def aggregate_bytes_per_elem(n):
+    return n * (1 + 1 / 8) + 4                    # read n code streams, write fp32
+
+
+def measured_traffic(name):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--quick", action="store_true", help="smaller d (for profiling runs); not a valid result")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="for `rocprofv3 --pmc` runs: a few steps plus 1 GiB device copies (the counter calibration), no timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    from paper_1905_10988_amd import natcomp as nc
+    from paper_1905_10988_amd import workloads as wl
+
+    nc.lib()                                       # fails loudly if libnatcomp.so is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    n = wl.NUM_WORKERS
+    d = wl.D_RESNET50 if not args.quick else wl.D_RESNET50 // 16
+    off = wl.layer_offsets(d=d) if not args.quick else wl.layer_offsets(d=d, hi=d // 8)
+    row = (d + 63) // 64 * 64
+    xdev = torch.empty((n, row), dtype=torch.float32, device="cuda")
+    x_host = []
+    for w in range(n):
+        xw = wl.layered_gaussian(w, off)
+        xdev[w, :d] = torch.from_numpy(xw).cuda()
+        x_host.append(xw)
+    exp = torch.empty((n, nc.plane_stride(nc.nat_exp_bytes(d))), dtype=torch.uint8, device="cuda")
+    sign = torch.empty((n, nc.plane_stride(nc.sign_bytes(d))), dtype=torch.uint8, device="cuda")
+    out = torch.empty(d, dtype=torch.float32, device="cuda")
+
+    def step(seed):
+        nc.nat_encode_batch(xdev, seed=seed, d=d, exp_out=exp, sign_out=sign)
+        nc.aggregate_sum(nc.NC_KIND_NAT, d, exp, sign, out=out)
+
+    if args.pmc_probe:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for i in range(3):
+            step(i)
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_probe": True, "copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4,
+                          "d": d, "n_workers": n}))
+        return
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps; HIP events on the launch stream bracket each kernel
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        ev[i][0].record()
+        nc.nat_encode_batch(xdev, seed=1000 + i, d=d, exp_out=exp, sign_out=sign)
+        ev[i][1].record()
+        nc.aggregate_sum(nc.NC_KIND_NAT, d, exp, sign, out=out)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    agg_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+
+    input_bytes = 4.0 * d * n
+    value = input_bytes / (ms_per_step * 1e-3) / 1e9
+    enc_alg = ENCODE_BYTES_PER_ELEM * d * n
+    agg_alg = aggregate_bytes_per_elem(n) * d
+    enc_gbs = enc_alg / (enc_ms * 1e-3) / 1e9
+    agg_gbs = agg_alg / (agg_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": "GB/s fp32 input encoded (C_nat) and decoded+summed (n=8)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32/f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "config 2: C_nat encode of 8 workers x d=25,557,032 fp32 (161 layers, N(0, sigma_l^2)), "
+                        "then fused decode+sum n=8" + (" [QUICK, reduced d: not a valid result]" if args.quick else ""),
+            "d": d, "n_workers": n, "launches_per_step": 2,
+        },
+        "roofline": {
+            "kernel": "nat_encode_kernel (8 workers in one launch)",
+            "bound": "hbm",
+            "achieved": round(enc_gbs, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(enc_gbs / HBM_PEAK_GBS, 4),
+            "traffic": measured_traffic("nat_encode_config2_pmc.txt"),
+            "algorithmic_bytes_per_launch": enc_alg,
+            "avg_launch_ms": round(enc_ms, 5),
+        },
+        "roofline_aggregate": {
+            "kernel": "nat_aggregate_kernel (n=8)",
+            "bound": "hbm",
+            "achieved": round(agg_gbs, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(agg_gbs / HBM_PEAK_GBS, 4),
+            "traffic": measured_traffic("nat_aggregate_config2_pmc.txt"),
+            "algorithmic_bytes_per_launch": agg_alg,
+            "avg_launch_ms": round(agg_ms, 5),
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        # the same step on the host: all 8 workers encoded by the oracle, then decoded and summed
+        # (it is short enough to run whole); rate per fp32 input byte, like `value`
+        exp_h = np.zeros((n, d), np.uint8)
+        sign_h = np.zeros((n, (d + 7) // 8), np.uint8)
+        t0 = time.perf_counter()
+        for w in range(n):
+            exp_h[w], sign_h[w] = oracle.nat_encode(x_host[w], 1000, w)
+        oracle.aggregate_nat(exp_h, sign_h, d)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {
+            "value": round(n * 4.0 * d / dt / 1e9, 3),
+            "unit": "GB/s",
+            "cores": oracle.threads(),
+            "kind": "oracle",
+            "sample": f"one whole step (8 workers x d={d} encoded, 8 streams decoded+summed), {dt:.2f} s of wall time",
+        }
+        # cross-check the GPU result of the last step on a window while we are here
+        a, b = 0, 4096
+        eo, so = oracle.nat_encode(x_host[0][a:b], 1000 + K - 1, 0, index_offset=a)
+        assert np.array_equal(exp[0, a:b].cpu().numpy(), eo), "GPU codes differ from the oracle"
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -70,8 +70,15 @@ def lib():
         L.orc_aggregate_dither.argtypes = [_f32p, _u64, _u8p, _u64, _u8p, _u64, _u32, _u64, _u64p, _u32, _u32, _u32,
                                            _f64p, _f32p, _f64p]
         L.orc_aggregate_dither.restype = None
+        L.orc_threads.argtypes = []
+        L.orc_threads.restype = ctypes.c_int
         _lib = L
     return _lib
+
+
+def threads():
+    """OpenMP threads the element-parallel loops use."""
+    return int(lib().orc_threads())
 
 
 def _ptr(a, typ):

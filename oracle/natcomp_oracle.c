@@ -427,3 +427,11 @@ void orc_aggregate_dither(const float *norms, uint64_t norm_stride, const uint8_
         }
     }
 }
+
+/* Number of threads the "parallel for" loops above use (for reporting timings). */
+#ifdef _OPENMP
+#include <omp.h>
+int orc_threads(void) { return omp_get_max_threads(); }
+#else
+int orc_threads(void) { return 1; }
+#endif
