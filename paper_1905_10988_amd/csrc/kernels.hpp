@@ -25,6 +25,41 @@ struct NatAggregateArgs {
     uint32_t n; uint64_t d; float* out;
 };
 
+// Segment description shared by the dithering kernels: explicit offsets (num_segments+1
+// ascending values), or a fixed bucket length, or (both absent) one segment.
+struct Segs {
+    const uint64_t* offsets; uint32_t num_segments; uint32_t bucket; uint64_t d;
+};
+
+enum { kNormL1 = 1, kNormL2 = 2, kNormInf = 3 };
+// Code formats by bits per level code: fused nibble (sign<<3)|c, nibble + sign plane, byte + sign plane.
+enum { kFmtFused = 0, kFmtNibble = 1, kFmtByte = 2 };
+
+constexpr uint32_t kChunk = 2048;          // elements per workgroup in the chunked kernels (256 lanes x 8)
+constexpr uint32_t kMaxOnePassBucket = 8192;  // largest bucket one workgroup keeps in registers
+
+struct DitherEncodeArgs {
+    const float* x; Segs segs;
+    int pnorm; uint32_t s; int fmt;
+    uint32_t k0, k1, worker; uint64_t index_offset;
+    float* norms_out; uint8_t* code_out; uint8_t* sign_out;
+    double* first_partial;   // one per chunk      (two-pass path only)
+    double* head_partial;    // one per segment    (two-pass path only)
+    float* inv_norm;         // one per segment    (two-pass path only)
+};
+struct DitherAggregateArgs {
+    const float* norms; size_t norm_stride; const uint8_t* code; size_t code_stride;
+    const uint8_t* sign; size_t sign_stride;
+    uint32_t n; Segs segs; uint32_t s; int fmt; float* out;
+};
+
+// One-pass encoder for fixed buckets of at most kMaxOnePassBucket elements (a multiple of 8).
+hipError_t launch_dither_bucket_encode(const DitherEncodeArgs& a, bool fast, hipStream_t stream);
+// Two-pass encoder for any segment description: partial norms, per-segment finish, encode.
+hipError_t launch_dither_segment_encode(const DitherEncodeArgs& a, bool fast, hipStream_t stream);
+// Decode (n = 1) and fused decode-and-sum (n > 1) of dithering codes.
+hipError_t launch_dither_aggregate(const DitherAggregateArgs& a, bool fast, hipStream_t stream);
+
 // `fast` promises the alignment the vector path needs (checked by the caller).
 hipError_t launch_nat_encode(const NatEncodeArgs& a, uint32_t n, bool fast, hipStream_t stream);
 hipError_t launch_nat_decode(const NatDecodeArgs& a, bool fast, hipStream_t stream);

@@ -84,15 +84,99 @@ nc_status nc_nat_decode(const uint8_t* exp, const uint8_t* sign, uint64_t d, flo
     return from_hip(launch_nat_decode(a, fast, (hipStream_t)stream));
 }
 
-nc_status nc_dither_encode(const float*, uint64_t, const uint64_t*, uint32_t, uint32_t, float, uint32_t, uint64_t,
-                           uint32_t, uint64_t, float*, uint8_t*, uint8_t*, void*, size_t, void*) {
-    return NC_ERR_UNSUPPORTED;
+// Segment description checks shared by the dithering entry points.
+static nc_status check_segments(uint64_t d, const uint64_t* seg_offsets, uint32_t num_segments, uint32_t bucket,
+                                Segs* out) {
+    if (seg_offsets) {
+        if (num_segments == 0 || num_segments >= (1u << 31)) return NC_ERR_INVALID;
+    } else if (bucket) {
+        if ((d + bucket - 1) / bucket >= (1ull << 31)) return NC_ERR_INVALID;
+    }
+    out->offsets = seg_offsets;
+    out->num_segments = seg_offsets ? num_segments : 0;
+    out->bucket = seg_offsets ? 0 : bucket;
+    out->d = d;
+    return NC_OK;
 }
-nc_status nc_dither_decode(const float*, const uint8_t*, const uint8_t*, uint64_t, const uint64_t*, uint32_t,
-                           uint32_t, uint32_t, float*, void*) {
-    return NC_ERR_UNSUPPORTED;
+static inline bool one_pass_bucket(const uint64_t* seg_offsets, uint32_t bucket) {
+    return !seg_offsets && bucket >= 8 && bucket <= kMaxOnePassBucket && (bucket & 7) == 0;
 }
-size_t nc_dither_workspace_bytes(uint64_t, uint32_t, uint32_t, int) { return 0; }
+static inline int format_of(uint32_t s) {
+    const uint32_t b = code_width(s);
+    return b <= 3 ? kFmtFused : b == 4 ? kFmtNibble : kFmtByte;
+}
+static inline size_t align8(size_t v) { return (v + 7) & ~(size_t)7; }
+
+size_t nc_dither_workspace_bytes(uint64_t d, uint32_t num_segments, uint32_t bucket, int have_offsets) {
+    if (d == 0) return 0;
+    if (!have_offsets && one_pass_bucket(nullptr, bucket)) return 0;
+    const uint64_t nseg = nc_segment_count(d, num_segments, bucket, have_offsets);
+    const uint64_t chunks = (d + kChunk - 1) / kChunk;
+    return (size_t)(8 * chunks + 8 * nseg + align8(4 * nseg));
+}
+
+nc_status nc_dither_encode(const float* x, uint64_t d, const uint64_t* seg_offsets, uint32_t num_segments,
+                           uint32_t bucket, float p, uint32_t s, uint64_t seed, uint32_t worker,
+                           uint64_t index_offset, float* norms_out, uint8_t* code_out, uint8_t* sign_out,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+    if (!valid_s(s) || d > kMaxD) return NC_ERR_INVALID;
+    int pnorm;
+    if (p == 1.0f) pnorm = kNormL1;
+    else if (p == 2.0f) pnorm = kNormL2;
+    else if (isinf(p) && p > 0) pnorm = kNormInf;
+    else return NC_ERR_UNSUPPORTED;
+    if (d == 0) return NC_OK;
+    if (!x || !norms_out || !code_out) return NC_ERR_NULL;
+    const int fmt = format_of(s);
+    if (fmt != kFmtFused && !sign_out) return NC_ERR_NULL;
+    DitherEncodeArgs a{};
+    nc_status st = check_segments(d, seg_offsets, num_segments, bucket, &a.segs);
+    if (st != NC_OK) return st;
+    a.x = x; a.pnorm = pnorm; a.s = s; a.fmt = fmt;
+    a.k0 = (uint32_t)seed; a.k1 = (uint32_t)(seed >> 32); a.worker = worker; a.index_offset = index_offset;
+    a.norms_out = norms_out; a.code_out = code_out; a.sign_out = sign_out;
+    const bool fast = aligned(x, 16) && (index_offset & 3) == 0 && aligned(code_out, fmt == kFmtByte ? 8 : 4);
+    if (one_pass_bucket(seg_offsets, bucket))
+        return from_hip(launch_dither_bucket_encode(a, fast, (hipStream_t)stream));
+    const size_t need = nc_dither_workspace_bytes(d, num_segments, bucket, seg_offsets != nullptr);
+    if (!workspace || workspace_bytes < need || !aligned(workspace, 8)) return NC_ERR_WORKSPACE;
+    const uint64_t nseg = nc_segment_count(d, num_segments, bucket, seg_offsets != nullptr);
+    const uint64_t chunks = (d + kChunk - 1) / kChunk;
+    a.first_partial = static_cast<double*>(workspace);
+    a.head_partial = a.first_partial + chunks;
+    a.inv_norm = reinterpret_cast<float*>(a.head_partial + nseg);
+    return from_hip(launch_dither_segment_encode(a, fast, (hipStream_t)stream));
+}
+
+static nc_status dither_aggregate(const float* norms, size_t norm_stride, const uint8_t* code, size_t code_stride,
+                                  const uint8_t* sign, size_t sign_stride, uint32_t n, uint64_t d,
+                                  const uint64_t* seg_offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
+                                  float* out, void* stream) {
+    if (!valid_s(s) || d > kMaxD || n == 0) return NC_ERR_INVALID;
+    if (d == 0) return NC_OK;
+    if (!norms || !code || !out) return NC_ERR_NULL;
+    const int fmt = format_of(s);
+    if (fmt != kFmtFused && !sign) return NC_ERR_NULL;
+    DitherAggregateArgs a{};
+    nc_status st = check_segments(d, seg_offsets, num_segments, bucket, &a.segs);
+    if (st != NC_OK) return st;
+    if (n > 1) {
+        if (code_stride < nc_dither_code_bytes(d, s) || (fmt != kFmtFused && sign_stride < nc_dither_sign_bytes(d, s)) ||
+            norm_stride < nc_segment_count(d, num_segments, bucket, seg_offsets != nullptr))
+            return NC_ERR_INVALID;
+    }
+    a.norms = norms; a.norm_stride = norm_stride; a.code = code; a.code_stride = code_stride;
+    a.sign = sign; a.sign_stride = sign_stride; a.n = n; a.s = s; a.fmt = fmt; a.out = out;
+    const size_t ca = fmt == kFmtByte ? 8 : 4;
+    const bool fast = aligned(code, ca) && aligned(out, 16) && (n == 1 || (code_stride & (ca - 1)) == 0);
+    return from_hip(launch_dither_aggregate(a, fast, (hipStream_t)stream));
+}
+
+nc_status nc_dither_decode(const float* norms, const uint8_t* code, const uint8_t* sign, uint64_t d,
+                           const uint64_t* seg_offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
+                           float* out, void* stream) {
+    return dither_aggregate(norms, 0, code, 0, sign, 0, 1, d, seg_offsets, num_segments, bucket, s, out, stream);
+}
 
 nc_status nc_aggregate_sum(const nc_agg_desc* desc, float* out, void* stream) {
     if (!desc) return NC_ERR_NULL;
@@ -108,7 +192,9 @@ nc_status nc_aggregate_sum(const nc_agg_desc* desc, float* out, void* stream) {
         const bool fast = aligned(desc->code, 8) && aligned(out, 16) && (desc->n == 1 || (desc->code_stride & 7) == 0);
         return from_hip(launch_nat_aggregate(a, fast, (hipStream_t)stream));
     }
-    return NC_ERR_UNSUPPORTED;
+    return dither_aggregate(desc->norms, desc->norm_stride, desc->code, desc->code_stride, desc->sign,
+                            desc->sign_stride, desc->n, desc->d, desc->seg_offsets, desc->num_segments, desc->bucket,
+                            desc->s, out, stream);
 }
 
 }  // extern "C"

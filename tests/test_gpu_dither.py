@@ -1,0 +1,271 @@
+"""GPU parity of natural dithering: norms within 1e-5 (relative) of the oracle's double
+accumulation (the maximum-norm bit-exact); level codes and sign planes bit-exact once the
+oracle is fed the GPU's binary32 norms; decoded values bit-exact; the n-way sum bit-exact
+against the oracle's left-to-right binary32 sum and within 1e-5 * sum|v| of its double sum."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import Guarded, dev, host
+
+pytestmark = pytest.mark.gpu
+INF = math.inf
+
+
+@pytest.fixture(scope="module")
+def nc():
+    from paper_1905_10988_amd import natcomp
+    natcomp.lib()
+    assert torch.cuda.is_available()
+    return natcomp
+
+
+@pytest.fixture(scope="module")
+def wl():
+    from paper_1905_10988_amd import workloads
+    return workloads
+
+
+def check_norms(got, ref64, p):
+    if p == INF:
+        assert np.array_equal(got.astype(np.float64), ref64)
+    else:
+        assert np.all(np.abs(got.astype(np.float64) - ref64) <= 1e-5 * ref64)
+
+
+def roundtrip(nc, oracle, x, p, s, seed=3, worker=0, index_offset=0, offsets=None, bucket=0, xdev=None):
+    """Encode + decode on the GPU with guarded outputs and compare everything with the oracle."""
+    d = x.size
+    xdev = dev(x) if xdev is None else xdev
+    offdev = None if offsets is None else dev(offsets)
+    nseg = nc.segment_count(d, 0 if offsets is None else offsets.size - 1, bucket, offsets is not None)
+    norms_b = Guarded(nseg, torch.float32)
+    code_b = Guarded(nc.dither_code_bytes(d, s))
+    nsign = nc.dither_sign_bytes(d, s)
+    sign_b = Guarded(nsign) if nsign else None
+    nc.dither_encode(xdev, p, s, seed, worker, index_offset, seg_offsets=offdev, bucket=bucket,
+                     norms_out=norms_b.t, code_out=code_b.t, sign_out=None if sign_b is None else sign_b.t)
+    torch.cuda.synchronize()
+    norms, code = norms_b.check(), code_b.check()
+    sign = sign_b.check() if sign_b else np.zeros(0, np.uint8)
+    ref64 = oracle.pnorm_segments(x, p, offsets=offsets, bucket=bucket)
+    check_norms(norms, ref64, p)
+    co, so = oracle.dither_encode(x, s, norms, seed, worker, index_offset, offsets=offsets, bucket=bucket)
+    assert np.array_equal(code, co), f"codes differ at bytes {np.flatnonzero(code != co)[:8]}"
+    assert np.array_equal(sign, so), f"signs differ at bytes {np.flatnonzero(sign != so)[:8]}"
+    out_b = Guarded(d, torch.float32)
+    nc.dither_decode(norms_b.t, code_b.t, None if sign_b is None else sign_b.t, d, s, seg_offsets=offdev,
+                     bucket=bucket, out=out_b.t)
+    torch.cuda.synchronize()
+    y = out_b.check()
+    yo = oracle.dither_decode(norms, co, so if nsign else None, d, s, offsets=offsets, bucket=bucket)
+    assert np.array_equal(y.view(np.uint32), yo.view(np.uint32)), \
+        f"decoded values differ at {np.flatnonzero(y.view(np.uint32) != yo.view(np.uint32))[:8]}"
+    return norms, code, sign
+
+
+@pytest.mark.parametrize("s", [1, 3, 4, 7, 8, 15, 16, 40, 95, 96, 127])
+@pytest.mark.parametrize("p", [1, 2, INF])
+def test_levels_and_formats_bucketed(nc, oracle, wl, s, p):
+    """One-pass bucket encoder, all three code formats, both level formulas (s <= 95 and above)."""
+    x = wl.bucketed_gaussian(0, d=20011, bucket=512, seed=s)
+    roundtrip(nc, oracle, x, p, s, bucket=512)
+
+
+@pytest.mark.parametrize("bucket", [8, 64, 2048, 4096, 8192])
+def test_one_pass_bucket_sizes(nc, oracle, wl, bucket):
+    x = wl.bucketed_gaussian(1, d=5 * 8192 + 2856, bucket=bucket, seed=9)
+    roundtrip(nc, oracle, x, INF, 4, bucket=bucket)
+    roundtrip(nc, oracle, x, 2, 8, bucket=bucket)
+
+
+@pytest.mark.parametrize("bucket", [0, 100, 1000, 2047, 16384, 50000])
+def test_two_pass_buckets_and_whole_vector(nc, oracle, wl, bucket):
+    """Buckets that are not a multiple of 8, larger than a workgroup holds, and the single segment."""
+    x = wl.bucketed_gaussian(2, d=70001, bucket=max(bucket, 1), seed=10)
+    for p, s in [(INF, 4), (2, 8), (1, 20)]:
+        roundtrip(nc, oracle, x, p, s, bucket=bucket)
+
+
+def test_layer_segments(nc, oracle, wl):
+    """Per-layer norms (config 3 layout, scaled down): tiny layers, empty segments, boundaries
+    inside a group of 8 and inside a 2048-element chunk."""
+    d = 300_007
+    off = wl.layer_offsets(d=d, num_layers=41, lo=64, hi=60_000, seed=12)
+    x = wl.layered_laplace(0, off, seed=13)
+    for p, s in [(2, 8), (INF, 4), (1, 16)]:
+        roundtrip(nc, oracle, x, p, s, offsets=off)
+    off2 = np.array([0, 3, 3, 64, 65, 2048, 2050, 2050, 4099, 100_000, d], np.uint64)
+    for p, s in [(2, 8), (INF, 3), (1, 33)]:
+        roundtrip(nc, oracle, x, p, s, offsets=off2)
+    roundtrip(nc, oracle, x, 2, 8, offsets=np.array([0, d], np.uint64))
+
+
+@pytest.mark.parametrize("d", [1, 2, 7, 8, 9, 15, 17, 2047, 2049, 4097])
+def test_ragged_sizes(nc, oracle, wl, d):
+    x = wl.bucketed_gaussian(0, d=d, bucket=64, seed=d)
+    for s in (4, 8, 16):
+        roundtrip(nc, oracle, x, 2, s)
+        roundtrip(nc, oracle, x, INF, s, bucket=64)
+        roundtrip(nc, oracle, x, 1, s, bucket=24)
+
+
+@pytest.mark.parametrize("shift,index_offset", [(0, 4), (0, 1), (1, 0), (3, 6), (2, 2**34 + 4), (0, 2**35 + 3)])
+def test_unaligned_and_offsets(nc, oracle, wl, shift, index_offset):
+    d = 9001
+    base = wl.bucketed_gaussian(3, d=d + 8, bucket=128, seed=14)
+    x = base[shift: shift + d].copy()
+    xdev = dev(base)[shift: shift + d]
+    off = np.array([0, 100, 5000, d], np.uint64)
+    roundtrip(nc, oracle, x, INF, 4, index_offset=index_offset, bucket=128, xdev=xdev)
+    roundtrip(nc, oracle, x, 2, 8, index_offset=index_offset, offsets=off, xdev=xdev)
+    roundtrip(nc, oracle, x, 2, 20, index_offset=index_offset, xdev=xdev)
+
+
+def test_degenerate_values(nc, oracle, wl):
+    """Zero vector and zero buckets, a lone non-zero, exact levels, tiny norms whose decoded
+    values are subnormal, huge values, signed zeros."""
+    d = 4096
+    z = np.zeros(d, np.float32)
+    z[1000] = -0.0
+    norms, code, _ = roundtrip(nc, oracle, z, 2, 8)
+    assert norms[0] == 0 and not code.any()
+    one = z.copy()
+    one[777] = -3.5
+    roundtrip(nc, oracle, one, 2, 8, bucket=512)
+    roundtrip(nc, oracle, one, INF, 4, bucket=512)
+    lv = np.array([1.0, 0.5, 0.25, 0.125, 0.0625, -1.0, -0.125, 0.0] * 64, np.float32)
+    roundtrip(nc, oracle, lv, INF, 4)
+    roundtrip(nc, oracle, lv, INF, 3, bucket=64)
+    rng = np.random.default_rng(15)
+    tiny = (rng.standard_normal(d) * 1e-37).astype(np.float32)
+    roundtrip(nc, oracle, tiny, INF, 8, bucket=256)
+    roundtrip(nc, oracle, tiny, 2, 100, bucket=256)
+    sub = (rng.standard_normal(d) * 1e-41).astype(np.float32)        # all subnormal: norm below 2^-126
+    norms, code, _ = roundtrip(nc, oracle, sub, INF, 4)
+    assert 0 < norms[0] < 1.1754944e-38 and not (code & 0x77).any()    # level codes all zero, signs kept
+    huge = (rng.standard_normal(d) * 1e37).astype(np.float32)
+    roundtrip(nc, oracle, huge, INF, 4, bucket=256)
+    roundtrip(nc, oracle, huge * np.float32(1e-2), 1, 8, bucket=256)     # the 1-norm of a bucket stays finite
+    mixed = (rng.standard_normal(d) * np.exp2(rng.integers(-100, 100, d))).astype(np.float32)
+    for s in (4, 8, 60, 127):
+        roundtrip(nc, oracle, mixed, INF, s, bucket=512)
+        roundtrip(nc, oracle, mixed, 2, s)
+
+
+def test_dithering_reduces_to_natural_compression_on_gpu(nc, oracle):
+    """Power-of-two max-norm and s = 126: the GPU's level codes are C_nat's exponents for the
+    same random words (codes of the two operators come from different streams, so compare
+    through the oracle's rule on the dithering stream)."""
+    rng = np.random.default_rng(16)
+    d = 4096
+    x = (rng.uniform(-1, 1, d) * np.exp2(-rng.integers(0, 60, d))).astype(np.float32)
+    x[0] = 1.0
+    norms, code, sign = roundtrip(nc, oracle, x, INF, 126, seed=5)
+    assert norms[0] == 1.0
+    u = x.view(np.uint32)
+    for i in range(0, d, 37):
+        e = (int(u[i]) >> 23) & 255
+        if e < 2:
+            continue
+        r = oracle.random_word(5, 0, oracle.DOMAIN_DITHER, i)
+        assert int(code[i]) - 126 == oracle.nat_round(int(u[i]), r) - 127
+
+
+@pytest.mark.parametrize("n", [1, 2, 8, 9, 16, 17, 33])
+@pytest.mark.parametrize("s,p", [(4, INF), (8, 2), (20, 1)])
+def test_aggregate(nc, oracle, wl, n, s, p):
+    d, bucket = 3 * 8192 + 1001, 8192
+    xs = [wl.bucketed_gaussian(w, d=d, bucket=bucket, seed=17) for w in range(n)]
+    nseg = nc.segment_count(d, 0, bucket, False)
+    cs, ss = nc.plane_stride(nc.dither_code_bytes(d, s)), nc.plane_stride(max(nc.dither_sign_bytes(d, s), 1))
+    norms = torch.zeros((n, nseg), dtype=torch.float32, device="cuda")
+    code = torch.zeros((n, cs), dtype=torch.uint8, device="cuda")
+    sign = torch.zeros((n, ss), dtype=torch.uint8, device="cuda")
+    for w in range(n):
+        nc.dither_encode(dev(xs[w]), p, s, 21, worker=w, bucket=bucket, norms_out=norms[w], code_out=code[w],
+                         sign_out=sign[w])
+    out = Guarded(d, torch.float32)
+    nc.aggregate_sum(nc.NC_KIND_DITHER, d, code, sign if nc.dither_sign_bytes(d, s) else None, norms, s=s,
+                     bucket=bucket, out=out.t)
+    torch.cuda.synchronize()
+    got = out.check()
+    o64, o32, oa = oracle.aggregate_dither(host(norms), host(code), host(sign) if nc.dither_sign_bytes(d, s) else None,
+                                           d, s, bucket=bucket)
+    assert np.array_equal(got.view(np.uint32), o32.view(np.uint32))
+    assert np.all(np.abs(got.astype(np.float64) - o64) <= 1e-5 * oa)
+
+
+def test_aggregate_layer_segments_and_odd_strides(nc, oracle, wl):
+    d, n, s = 50_003, 5, 8
+    off = wl.layer_offsets(d=d, num_layers=23, lo=64, hi=20_000, seed=18)
+    offdev = dev(off)
+    nseg = off.size - 1
+    cs, ss = nc.dither_code_bytes(d, s) + 3, nc.dither_sign_bytes(d, s) + 1     # strides that break vector alignment
+    norms = torch.zeros((n, nseg + 2), dtype=torch.float32, device="cuda")
+    code = torch.zeros((n, cs), dtype=torch.uint8, device="cuda")
+    sign = torch.zeros((n, ss), dtype=torch.uint8, device="cuda")
+    for w in range(n):
+        x = wl.layered_laplace(w, off, seed=19)
+        nc.dither_encode(dev(x), 2, s, 22, worker=w, seg_offsets=offdev, norms_out=norms[w, :nseg],
+                         code_out=code[w, : cs - 3], sign_out=sign[w, : ss - 1])
+    got = host(nc.aggregate_sum(nc.NC_KIND_DITHER, d, code, sign, norms, s=s, seg_offsets=offdev))
+    o64, o32, oa = oracle.aggregate_dither(host(norms)[:, :nseg].copy(), host(code), host(sign), d, s, offsets=off)
+    assert np.array_equal(got.view(np.uint32), o32.view(np.uint32))
+    assert np.all(np.abs(got.astype(np.float64) - o64) <= 1e-5 * oa)
+
+
+def test_workspace_errors(nc):
+    x = torch.zeros(10000, dtype=torch.float32, device="cuda")
+    need = nc.dither_workspace_bytes(10000, 0, 0, False)
+    assert need > 0 and nc.dither_workspace_bytes(10000, 0, 512, False) == 0
+    small = torch.empty(need - 8, dtype=torch.uint8, device="cuda")
+    with pytest.raises(nc.NatcompError, match="WORKSPACE"):
+        nc.dither_encode(x, 2, 8, 0, workspace=small)
+    with pytest.raises(nc.NatcompError, match="UNSUPPORTED"):
+        nc.dither_encode(x, 3, 8, 0)
+    with pytest.raises(nc.NatcompError, match="INVALID"):
+        nc.dither_encode(x, 2, 128, 0, code_out=torch.empty(10000, dtype=torch.uint8, device="cuda"),
+                         sign_out=torch.empty(2000, dtype=torch.uint8, device="cuda"))
+
+
+def test_config3_full_size(nc, oracle, wl):
+    """Config 3 at full size: D_nat^{2,8}, norm per layer tensor (161 layers, d = 25,557,032),
+    Laplace entries; 1 sign bit + 4-bit code per entry; encode then decode."""
+    off = wl.layer_offsets()
+    x = wl.layered_laplace(0, off)
+    roundtrip(nc, oracle, x, 2, 8, seed=0, offsets=off)
+
+
+def test_config4_full_size_two_workers(nc, oracle, wl):
+    """Config 4 at its full d = 138,357,544 (buckets of 8192, max-norm, s = 4) with two of the
+    eight workers: both planes in full against the oracle, the fused sum on windows."""
+    d, bucket, s = wl.D_VGG16, wl.BUCKET, 4
+    n = 2
+    nseg = nc.segment_count(d, 0, bucket, False)
+    cs = nc.plane_stride(nc.dither_code_bytes(d, s))
+    norms = torch.zeros((n, nseg), dtype=torch.float32, device="cuda")
+    code = torch.zeros((n, cs), dtype=torch.uint8, device="cuda")
+    xs = []
+    for w in range(n):
+        x = wl.bucketed_gaussian(w)
+        xs.append(x)
+        nc.dither_encode(torch.from_numpy(x).cuda(), INF, s, 0, worker=w, bucket=bucket, norms_out=norms[w],
+                         code_out=code[w])
+    out = nc.aggregate_sum(nc.NC_KIND_DITHER, d, code, None, norms, s=s, bucket=bucket)
+    torch.cuda.synchronize()
+    norms_h, code_h, got = host(norms), host(code), host(out)
+    for w in range(n):
+        assert np.array_equal(norms_h[w].astype(np.float64), oracle.pnorm_segments(xs[w], INF, bucket=bucket))
+    co0, _ = oracle.dither_encode(xs[0], s, norms_h[0], 0, 0, bucket=bucket)
+    assert np.array_equal(code_h[0, : co0.size], co0)
+    rng = np.random.default_rng(2)
+    for b in [0, nseg - 1] + rng.integers(0, nseg - 1, 6).tolist():
+        a0, a1 = b * bucket, min((b + 1) * bucket, d)
+        cw = np.stack([oracle.dither_encode(xs[w][a0:a1], s, norms_h[w, b:b + 1], 0, w, index_offset=a0)[0] for w in range(n)])
+        assert np.array_equal(code_h[:, a0 // 2: a0 // 2 + cw.shape[1]], cw)
+        o64, o32, oa = oracle.aggregate_dither(norms_h[:, b:b + 1].copy(), cw, None, a1 - a0, s)
+        assert np.array_equal(got[a0:a1].view(np.uint32), o32.view(np.uint32))
+        assert np.all(np.abs(got[a0:a1].astype(np.float64) - o64) <= 1e-5 * oa)
