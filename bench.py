@@ -37,12 +37,84 @@ def measured_traffic(name):
         return None
 
 
+def _time_ms(torch, np, fn, reps=20, warm=3):
+    """Average HIP-event time of fn() on the current stream."""
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return float(np.mean([a.elapsed_time(b) for a, b in evs]))
+
+
+def _entry(ms, alg_bytes, input_bytes, note):
+    gbs = alg_bytes / (ms * 1e-3) / 1e9
+    return {"ms": round(ms, 5), "algorithmic_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+            "fp32_input_GBps": round(input_bytes / (ms * 1e-3) / 1e9, 1), "algorithmic_bytes": alg_bytes, "note": note}
+
+
+def secondary_kernels(nc, wl, torch, np):
+    """The remaining kernels of the path, each on its configuration's shape (not part of `value`)."""
+    import math
+    res = {}
+    d = wl.D_RESNET50
+    off = wl.layer_offsets()
+    offdev = torch.from_numpy(off.view(np.int64)).cuda()
+    nseg = off.size - 1
+    x = wl.layered_laplace_device(0, off)
+    out = torch.empty(d, dtype=torch.float32, device="cuda")
+    # C_nat decode of one worker (config 2 shape)
+    e, sg = nc.nat_encode(x, 0)
+    ms = _time_ms(torch, np, lambda: nc.nat_decode(e, sg, d, out=out))
+    res["nat_decode_d25.6M"] = _entry(ms, (1.125 + 4) * d, 4.0 * d, "1.125 B read + 4 B written per element")
+    # config 3: D_nat^{2,8}, norm per layer tensor, encode then decode
+    norms = torch.empty(nseg, dtype=torch.float32, device="cuda")
+    code = torch.empty(nc.dither_code_bytes(d, 8), dtype=torch.uint8, device="cuda")
+    sign = torch.empty(nc.dither_sign_bytes(d, 8), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(nc.dither_workspace_bytes(d, nseg, 0, True), dtype=torch.uint8, device="cuda")
+    ms = _time_ms(torch, np, lambda: nc.dither_encode(x, 2, 8, 0, seg_offsets=offdev, norms_out=norms, code_out=code,
+                                                      sign_out=sign, workspace=ws))
+    res["config3_dither_2_8_layer_encode"] = _entry(
+        ms, 4.625 * d, 4.0 * d, "3 launches (partial norms, finish, encode); minimum 4 + 0.625 B per element, "
+        "this two-pass path moves 8 + 0.625 unless the second read hits the last-level cache")
+    ms = _time_ms(torch, np, lambda: nc.dither_decode(norms, code, sign, d, 8, seg_offsets=offdev, out=out))
+    res["config3_dither_2_8_layer_decode"] = _entry(ms, 4.625 * d, 4.0 * d, "0.625 B read + 4 B written per element")
+    del x, out, code, sign, e, sg
+    # config 4: D_nat^{inf,4}, buckets of 8192, 8 workers, fused decode+sum
+    d4, n, bucket = wl.D_VGG16, wl.NUM_WORKERS, wl.BUCKET
+    nb = nc.segment_count(d4, 0, bucket, False)
+    xs = torch.empty((n, d4), dtype=torch.float32, device="cuda")
+    for w in range(n):
+        wl.bucketed_gaussian_device(w, out=xs[w])
+    norms4 = torch.empty((n, nb), dtype=torch.float32, device="cuda")
+    code4 = torch.empty((n, nc.plane_stride(nc.dither_code_bytes(d4, 4))), dtype=torch.uint8, device="cuda")
+    out4 = torch.empty(d4, dtype=torch.float32, device="cuda")
+
+    def encode_all():
+        for w in range(n):
+            nc.dither_encode(xs[w], math.inf, 4, 0, worker=w, bucket=bucket, norms_out=norms4[w], code_out=code4[w])
+
+    ms = _time_ms(torch, np, encode_all, reps=10)
+    res["config4_dither_inf_4_bucket_encode_x8"] = _entry(ms, 4.5 * d4 * n, 4.0 * d4 * n,
+                                                         "8 one-pass launches; 4 + 0.5 B per element")
+    ms = _time_ms(torch, np, lambda: nc.aggregate_sum(nc.NC_KIND_DITHER, d4, code4, None, norms4, s=4, bucket=bucket,
+                                                      out=out4), reps=10)
+    res["config4_dither_inf_4_aggregate_n8"] = _entry(ms, 8.0 * d4 + 4.0 * nb * n, 4.0 * d4 * n,
+                                                     "8 x 0.5 B read + 4 B written per output element, plus norms")
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-secondary", action="store_true", help="skip the other kernels (decode, dithering configs 3 and 4)")
     ap.add_argument("--quick", action="store_true", help="smaller d (for profiling runs); not a valid result")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for `rocprofv3 --pmc` runs: a few steps plus 1 GiB device copies (the counter calibration), no timing")
@@ -157,6 +229,9 @@ def main():
             "avg_launch_ms": round(agg_ms, 5),
         },
     }
+
+    if not args.no_secondary and not args.quick:
+        result["other_kernels"] = secondary_kernels(nc, wl, torch, np)
 
     if not args.no_cpu_baseline:
         import oracle
