@@ -78,7 +78,7 @@ size_t nc_dither_workspace_bytes(uint64_t d, uint32_t num_segments, uint32_t buc
  *
  *   x         DEVICE, d floats.
  *   exp_out   DEVICE, nc_nat_exp_bytes(d) bytes.     sign_out  DEVICE, nc_sign_bytes(d) bytes.
- * Fastest when x is 16-byte aligned, exp_out 8-byte aligned and index_offset a multiple
+ * Fastest when x is 16-byte aligned, exp_out and sign_out 4-byte aligned and index_offset a multiple
  * of 4; any alignment and offset is accepted.
  * -------------------------------------------------------------------------------------- */
 nc_status nc_nat_encode(const float *x, uint64_t d, uint64_t seed, uint32_t worker,

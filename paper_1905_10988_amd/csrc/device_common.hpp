@@ -84,6 +84,22 @@ __device__ __forceinline__ uint32_t push_sign(uint32_t acc, uint32_t u) {
     return __builtin_amdgcn_alignbit(acc, u, 31);
 }
 
+// Lane i receives v from lane i+N of its row of 16 lanes (DPP row_shl:N); lanes whose source
+// falls outside the row receive 0.  All lanes of the wavefront must be active.
+template <int N>
+__device__ __forceinline__ uint32_t from_lane_plus(uint32_t v) {
+    return __builtin_amdgcn_update_dpp(0u, v, 0x100 + N, 0xF, 0xF, true);
+}
+
+// Each lane holds a 4-bit value; the word returned in lanes with (lane mod 8) == 0 packs the
+// nibbles of lanes lane .. lane+7, lowest lane in the lowest nibble.
+__device__ __forceinline__ uint32_t gather_nibbles8(uint32_t nib) {
+    uint32_t t = nib | (from_lane_plus<1>(nib) << 4);
+    t |= from_lane_plus<2>(t) << 8;
+    t |= from_lane_plus<4>(t) << 16;
+    return t;
+}
+
 // Byte 3 of four registers packed into one word: result byte j = top byte of yj.
 __device__ __forceinline__ uint32_t pack_top_bytes(uint32_t y0, uint32_t y1, uint32_t y2, uint32_t y3) {
     const uint32_t lo = __builtin_amdgcn_perm(y1, y0, 0x0c0c0703u);  // bytes: [y0.b3, y1.b3, 0, 0]

@@ -1,15 +1,23 @@
 // Natural compression C_nat on gfx950: encoder, decoder and the fused n-worker
 // decode-and-sum (Sec. 2, Def. 1 and the binary32 derivation; Algorithm 1's master sum).
 //
-// Work split: one lane owns 8 consecutive elements.  It reads them with two 16-byte
-// loads, draws its 8 random words with two Philox calls, and writes 8 exponent bytes as
-// one 8-byte store plus one sign byte, so a wavefront reads 2 KiB and writes 512 + 64
-// contiguous bytes; no cross-lane traffic is needed.  The kernels are HBM-bound:
-// 5.125 bytes per encoded element, 8*1.125 + 4 bytes per summed element at n = 8.
+// All three kernels are HBM-bound streams: 5.125 bytes per encoded element,
+// 8*1.125 + 4 bytes per summed element at n = 8.  What decides their speed is the shape of
+// the memory instructions, so every global access of the vector paths is lane-contiguous:
+//   encoder  a workgroup owns a tile of 1024 elements; lane t reads the two 16-byte quads
+//            t and t+128 of the tile, draws one Philox call per quad, stores its four
+//            exponent bytes as one word per quad; the four sign bits of 8 neighbouring
+//            lanes are gathered with DPP row shifts into one word stored by every 8th lane;
+//   decoder / aggregate  lane t reads 8 exponent bytes and one sign byte per worker, builds
+//            8 floats, and the workgroup transposes them through LDS so that each store
+//            instruction writes 16 contiguous bytes per lane.
 #include "device_common.hpp"
 #include "kernels.hpp"
 
 namespace natcomp {
+
+constexpr int kEncBlock = 128;        // lanes per encoder workgroup
+constexpr uint32_t kEncTile = 1024;   // elements per encoder workgroup (128 lanes x 2 quads)
 
 // New exponent byte in the top byte of the result.  With u = (sign, e, m) and T = m * 2^9
 // the rule is "exponent + 1 iff r < T".  Since T is a multiple of 2^9 this is
@@ -20,8 +28,21 @@ __device__ __forceinline__ uint32_t nat_round_top(uint32_t u, uint32_t r_complem
     return add_sat(u << 1, r_complement >> 8);
 }
 
-// One group of up to 8 elements starting at local index i0, any alignment: scalar loads,
-// one Philox call per run of elements sharing a counter.
+// Four elements -> their four new exponent bytes in one word.
+__device__ __forceinline__ uint32_t nat_round_quad(u32x4 v, const uint32_t rc[4]) {
+    return pack_top_bytes(nat_round_top(v.x, rc[0]), nat_round_top(v.y, rc[1]), nat_round_top(v.z, rc[2]),
+                          nat_round_top(v.w, rc[3]));
+}
+// Sign bits of four elements, element 0 in bit 0.
+__device__ __forceinline__ uint32_t sign_nibble(u32x4 v) {
+    uint32_t s = v.w >> 31;
+    s = push_sign(s, v.z);
+    s = push_sign(s, v.y);
+    return push_sign(s, v.x);
+}
+
+// One group of up to 8 elements starting at local index i0 (a multiple of 8), any
+// alignment: scalar loads, one Philox call per run of elements sharing a counter.
 __device__ __noinline__ void nat_encode_group_generic(const float* __restrict__ x, uint64_t d, uint64_t i0,
                                                       uint64_t index_offset, uint32_t worker, uint32_t k0,
                                                       uint32_t k1, uint8_t* __restrict__ exp_out,
@@ -46,40 +67,57 @@ __device__ __noinline__ void nat_encode_group_generic(const float* __restrict__ 
     sign_out[i0 >> 3] = (uint8_t)sign_byte;
 }
 
-template <bool FAST>
-__global__ __launch_bounds__(kBlock) void nat_encode_kernel(NatEncodeArgs a) {
+// Vector encoder.  Requires: x 16-byte aligned, exp_out and sign_out 4-byte aligned,
+// index_offset a multiple of 4 (and the same for every worker's planes).  Elements
+// [0, 32*floor(d/32)) go through the vector path; the last d mod 32 through the scalar one.
+// A workgroup of 128 lanes owns 1024 elements: lane t takes quads t and t+128, and both
+// 16-byte loads are issued before any arithmetic (measured best among 64..512 lanes and
+// 1..4 quads per lane).
+__global__ __launch_bounds__(kEncBlock) void nat_encode_kernel(NatEncodeArgs a) {
     const uint32_t w = blockIdx.y;
     const float* __restrict__ x = a.x + (size_t)w * a.x_stride;
     uint8_t* __restrict__ exp_out = a.exp_out + (size_t)w * a.exp_stride;
     uint8_t* __restrict__ sign_out = a.sign_out + (size_t)w * a.sign_stride;
     const uint32_t worker = a.first_worker + w;
-    const uint64_t grp = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    const uint64_t i0 = grp * 8;
-    if (i0 >= a.d) return;
-    if (FAST && i0 + 8 <= a.d) {
-        const u32x4* __restrict__ xv = reinterpret_cast<const u32x4*>(x);
-        const u32x4 v0 = load_stream(xv + 2 * grp);
-        const u32x4 v1 = load_stream(xv + 2 * grp + 1);
-        const uint64_t q = (a.index_offset + i0) >> 2;  // index_offset is a multiple of 4 here
-        uint32_t r0[4], r1[4];
-        random_words4<true>(q, worker, kDomainNat, a.k0, a.k1, r0);
-        random_words4<true>(q + 1, worker, kDomainNat, a.k0, a.k1, r1);
-        const uint32_t y0 = nat_round_top(v0.x, r0[0]), y1 = nat_round_top(v0.y, r0[1]);
-        const uint32_t y2 = nat_round_top(v0.z, r0[2]), y3 = nat_round_top(v0.w, r0[3]);
-        const uint32_t y4 = nat_round_top(v1.x, r1[0]), y5 = nat_round_top(v1.y, r1[1]);
-        const uint32_t y6 = nat_round_top(v1.z, r1[2]), y7 = nat_round_top(v1.w, r1[3]);
-        uint32_t sg = v1.w >> 31;
-        sg = push_sign(sg, v1.z); sg = push_sign(sg, v1.y); sg = push_sign(sg, v1.x);
-        sg = push_sign(sg, v0.w); sg = push_sign(sg, v0.z); sg = push_sign(sg, v0.y);
-        sg = push_sign(sg, v0.x);
-        u32x2 packed;
-        packed.x = pack_top_bytes(y0, y1, y2, y3);
-        packed.y = pack_top_bytes(y4, y5, y6, y7);
-        store_stream(reinterpret_cast<u32x2*>(exp_out) + grp, packed);
-        store_stream(sign_out + grp, (uint8_t)sg);
-    } else {
-        nat_encode_group_generic(x, a.d, i0, a.index_offset, worker, a.k0, a.k1, exp_out, sign_out);
+    const uint64_t vec_quads = (a.d >> 5) << 3;  // quads inside whole 32-element groups
+    const uint64_t q0 = (uint64_t)blockIdx.x * (kEncTile / 4) + threadIdx.x;
+    const uint64_t qbase = a.index_offset >> 2;
+    const u32x4* __restrict__ xv = reinterpret_cast<const u32x4*>(x);
+    uint32_t* __restrict__ ev = reinterpret_cast<uint32_t*>(exp_out);
+    uint32_t* __restrict__ sv = reinterpret_cast<uint32_t*>(sign_out);
+    u32x4 v[2];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const uint64_t q = q0 + half * kEncBlock;
+        v[half] = u32x4{0u, 0u, 0u, 0u};
+        if (q < vec_quads) v[half] = load_stream(xv + q);
     }
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const uint64_t q = q0 + half * kEncBlock;
+        const bool in = q < vec_quads;  // uniform over each run of 8 lanes
+        uint32_t rc[4];
+        random_words4<true>(qbase + q, worker, kDomainNat, a.k0, a.k1, rc);
+        const uint32_t exps = nat_round_quad(v[half], rc);
+        const uint32_t packed = gather_nibbles8(sign_nibble(v[half]));  // every lane takes part
+        if (in) store_stream(ev + q, exps);
+        if (in && (threadIdx.x & 7) == 0) store_stream(sv + (q >> 3), packed);
+    }
+    // scalar tail: at most 31 elements, four groups of 8
+    const uint64_t tail0 = vec_quads * 4;
+    if (tail0 < a.d && blockIdx.x == gridDim.x - 1 && threadIdx.x < 4) {
+        const uint64_t i0 = tail0 + threadIdx.x * 8;
+        if (i0 < a.d) nat_encode_group_generic(x, a.d, i0, a.index_offset, worker, a.k0, a.k1, exp_out, sign_out);
+    }
+}
+
+// Any alignment: one group of 8 elements per lane.
+__global__ __launch_bounds__(kBlock) void nat_encode_generic_kernel(NatEncodeArgs a) {
+    const uint32_t w = blockIdx.y;
+    const uint64_t i0 = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 8;
+    if (i0 >= a.d) return;
+    nat_encode_group_generic(a.x + (size_t)w * a.x_stride, a.d, i0, a.index_offset, a.first_worker + w, a.k0, a.k1,
+                             a.exp_out + (size_t)w * a.exp_stride, a.sign_out + (size_t)w * a.sign_stride);
 }
 
 // Value of one coded element: sign and exponent from the planes, mantissa zero.
@@ -102,107 +140,158 @@ __device__ __forceinline__ void nat_decode8(u32x2 e, uint32_t sb, uint32_t v[8])
     v[7] = bitfield_insert(kExpMask, e.y >> 1, sb << 24);
 }
 
-template <bool FAST>
+// Writes the workgroup's tile of results: lane t put its 8 values into LDS slots 2t, 2t+1;
+// now every lane stores slots t and t+256, i.e. 16 contiguous bytes per lane per instruction.
+// `groups` = number of whole groups of 8 in the tile (the others are not stored here).
+__device__ __forceinline__ void store_tile_transposed(u32x4* lds, const uint32_t v[8], bool have, uint32_t groups,
+                                                      float* __restrict__ out_tile) {
+    if (have) {
+        lds[2 * threadIdx.x] = u32x4{v[0], v[1], v[2], v[3]};
+        lds[2 * threadIdx.x + 1] = u32x4{v[4], v[5], v[6], v[7]};
+    }
+    __syncthreads();
+    u32x4* __restrict__ o = reinterpret_cast<u32x4*>(out_tile);
+    if (threadIdx.x < 2 * groups) store_stream(o + threadIdx.x, lds[threadIdx.x]);
+    if (threadIdx.x + kBlock < 2 * groups) store_stream(o + threadIdx.x + kBlock, lds[threadIdx.x + kBlock]);
+}
+
+// Vector decoder.  Requires exp 8-byte aligned and out 16-byte aligned.
 __global__ __launch_bounds__(kBlock) void nat_decode_kernel(NatDecodeArgs a) {
-    const uint64_t grp = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    const uint64_t i0 = grp * 8;
-    if (i0 >= a.d) return;
-    if (FAST && i0 + 8 <= a.d) {
+    __shared__ u32x4 lds[2 * kBlock];
+    const uint64_t g0 = (uint64_t)blockIdx.x * kBlock;
+    const uint64_t grp = g0 + threadIdx.x;
+    const uint64_t full = a.d >> 3;  // whole groups of 8
+    const bool have = grp < full;
+    uint32_t v[8];
+    if (have) {
         const u32x2 e = load_stream(reinterpret_cast<const u32x2*>(a.exp) + grp);
         const uint32_t sb = load_stream(a.sign + grp);
-        uint32_t v[8];
         nat_decode8(e, sb, v);
-        u32x4* __restrict__ o = reinterpret_cast<u32x4*>(a.out) + 2 * grp;
-        store_stream(o, u32x4{v[0], v[1], v[2], v[3]});
-        store_stream(o + 1, u32x4{v[4], v[5], v[6], v[7]});
-    } else {
-        const uint32_t sb = a.sign[i0 >> 3];
-        for (int j = 0; j < 8; ++j) {
-            const uint64_t i = i0 + j;
-            if (i >= a.d) break;
-            a.out[i] = bits_f32(nat_value_bits(a.exp[i], (sb >> j) & 1u));
-        }
+    }
+    const uint32_t groups = full - g0 < kBlock ? (uint32_t)(full - g0) : (uint32_t)kBlock;
+    store_tile_transposed(lds, v, have, full > g0 ? groups : 0u, a.out + g0 * 8);
+    if (grp == full && (a.d & 7)) {  // the ragged last group
+        const uint32_t sb = a.sign[grp];
+        for (uint64_t i = grp * 8; i < a.d; ++i) a.out[i] = bits_f32(nat_value_bits(a.exp[i], (sb >> (i & 7)) & 1u));
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void nat_decode_generic_kernel(NatDecodeArgs a) {
+    const uint64_t i0 = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 8;
+    if (i0 >= a.d) return;
+    const uint32_t sb = a.sign[i0 >> 3];
+    for (int j = 0; j < 8; ++j) {
+        const uint64_t i = i0 + j;
+        if (i >= a.d) break;
+        a.out[i] = bits_f32(nat_value_bits(a.exp[i], (sb >> j) & 1u));
+    }
+}
+
+// One element of the sum, any alignment: workers added left to right from worker 0's value.
+__device__ __forceinline__ float nat_sum_one(const NatAggregateArgs& a, uint64_t i) {
+    float acc = 0.0f;
+    for (uint32_t w = 0; w < a.n; ++w) {
+        const uint32_t eb = a.exp[(size_t)w * a.exp_stride + i];
+        const uint32_t sg = (a.sign[(size_t)w * a.sign_stride + (i >> 3)] >> (i & 7)) & 1u;
+        const float v = bits_f32(nat_value_bits(eb, sg));
+        acc = (w == 0) ? v : acc + v;
+    }
+    return acc;
+}
+
+// NW workers starting at w0: all 2*NW loads are issued before the first add.
+template <int NW>
+__device__ __forceinline__ void nat_sum_chunk(const NatAggregateArgs& a, uint64_t grp, uint32_t w0, float acc[8]) {
+    u32x2 e[NW];
+    uint32_t sb[NW];
+#pragma unroll
+    for (int k = 0; k < NW; ++k) {
+        const size_t w = w0 + k;
+        e[k] = load_stream(reinterpret_cast<const u32x2*>(a.exp + w * a.exp_stride) + grp);
+        sb[k] = load_stream(a.sign + w * a.sign_stride + grp);
+    }
+#pragma unroll
+    for (int k = 0; k < NW; ++k) {
+        uint32_t v[8];
+        nat_decode8(e[k], sb[k], v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += bits_f32(v[j]);
     }
 }
 
 // Fused decode-and-sum over n workers, 8 output elements per lane.  Workers are taken in
 // chunks of up to 8 whose loads are all issued before the first add, and added in the
 // fixed order w = 0, 1, ..., n-1 starting from worker 0's value.
-template <bool FAST>
+// Requires every worker's exponent plane 8-byte aligned and out 16-byte aligned.
 __global__ __launch_bounds__(kBlock) void nat_aggregate_kernel(NatAggregateArgs a) {
-    const uint64_t grp = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    const uint64_t i0 = grp * 8;
-    if (i0 >= a.d) return;
-    if (FAST && i0 + 8 <= a.d) {
-        float acc[8];
-        for (uint32_t w0 = 0; w0 < a.n; w0 += 8) {
-            u32x2 e[8];
-            uint32_t sb[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                if (w0 + k < a.n) {
-                    const size_t w = w0 + k;
-                    e[k] = load_stream(reinterpret_cast<const u32x2*>(a.exp + w * a.exp_stride) + grp);
-                    sb[k] = load_stream(a.sign + w * a.sign_stride + grp);
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                if (w0 + k < a.n) {
-                    uint32_t v[8];
-                    nat_decode8(e[k], sb[k], v);
-                    if (w0 + k == 0) {
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) acc[j] = bits_f32(v[j]);
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) acc[j] += bits_f32(v[j]);
-                    }
-                }
-            }
+    __shared__ u32x4 lds[2 * kBlock];
+    const uint64_t g0 = (uint64_t)blockIdx.x * kBlock;
+    const uint64_t grp = g0 + threadIdx.x;
+    const uint64_t full = a.d >> 3;
+    const bool have = grp < full;
+    uint32_t bits[8];
+    if (have) {
+        // -0.0 is the identity of binary32 addition (x + -0.0 == x bit for bit, signed zeros
+        // included), so starting there equals starting from worker 0's value.
+        float acc[8] = {-0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f};
+        uint32_t w0 = 0;
+        for (; w0 + 8 <= a.n; w0 += 8) nat_sum_chunk<8>(a, grp, w0, acc);
+        switch (a.n - w0) {
+            case 1: nat_sum_chunk<1>(a, grp, w0, acc); break;
+            case 2: nat_sum_chunk<2>(a, grp, w0, acc); break;
+            case 3: nat_sum_chunk<3>(a, grp, w0, acc); break;
+            case 4: nat_sum_chunk<4>(a, grp, w0, acc); break;
+            case 5: nat_sum_chunk<5>(a, grp, w0, acc); break;
+            case 6: nat_sum_chunk<6>(a, grp, w0, acc); break;
+            case 7: nat_sum_chunk<7>(a, grp, w0, acc); break;
+            default: break;
         }
-        u32x4* __restrict__ o = reinterpret_cast<u32x4*>(a.out) + 2 * grp;
-        store_stream(o, u32x4{f32_bits(acc[0]), f32_bits(acc[1]), f32_bits(acc[2]), f32_bits(acc[3])});
-        store_stream(o + 1, u32x4{f32_bits(acc[4]), f32_bits(acc[5]), f32_bits(acc[6]), f32_bits(acc[7])});
-    } else {
-        for (int j = 0; j < 8; ++j) {
-            const uint64_t i = i0 + j;
-            if (i >= a.d) break;
-            float acc = 0.0f;
-            for (uint32_t w = 0; w < a.n; ++w) {
-                const uint32_t eb = a.exp[(size_t)w * a.exp_stride + i];
-                const uint32_t sg = (a.sign[(size_t)w * a.sign_stride + (i >> 3)] >> (i & 7)) & 1u;
-                const float v = bits_f32(nat_value_bits(eb, sg));
-                acc = (w == 0) ? v : acc + v;
-            }
-            a.out[i] = acc;
-        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) bits[j] = f32_bits(acc[j]);
+    }
+    const uint32_t groups = full - g0 < kBlock ? (uint32_t)(full - g0) : (uint32_t)kBlock;
+    store_tile_transposed(lds, bits, have, full > g0 ? groups : 0u, a.out + g0 * 8);
+    if (grp == full && (a.d & 7)) {
+        for (uint64_t i = grp * 8; i < a.d; ++i) a.out[i] = nat_sum_one(a, i);
     }
 }
 
+__global__ __launch_bounds__(kBlock) void nat_aggregate_generic_kernel(NatAggregateArgs a) {
+    const uint64_t i0 = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 8;
+    for (int j = 0; j < 8; ++j) {
+        const uint64_t i = i0 + j;
+        if (i >= a.d) break;
+        a.out[i] = nat_sum_one(a, i);
+    }
+}
+
+// One lane per group of 8 elements; the grid always covers the ragged last group too.
 static inline dim3 grid_for_groups(uint64_t d, uint32_t y) {
-    const uint64_t groups = (d + 7) / 8;
+    const uint64_t groups = d / 8 + 1;
     return dim3((unsigned)((groups + kBlock - 1) / kBlock), y, 1);
 }
 
 hipError_t launch_nat_encode(const NatEncodeArgs& a, uint32_t n, bool fast, hipStream_t stream) {
-    const dim3 grid = grid_for_groups(a.d, n);
-    if (fast) nat_encode_kernel<true><<<grid, kBlock, 0, stream>>>(a);
-    else nat_encode_kernel<false><<<grid, kBlock, 0, stream>>>(a);
+    if (fast) {
+        const dim3 grid((unsigned)((a.d + kEncTile - 1) / kEncTile), n, 1);
+        nat_encode_kernel<<<grid, kEncBlock, 0, stream>>>(a);
+    } else {
+        nat_encode_generic_kernel<<<grid_for_groups(a.d, n), kBlock, 0, stream>>>(a);
+    }
     return hipGetLastError();
 }
 
 hipError_t launch_nat_decode(const NatDecodeArgs& a, bool fast, hipStream_t stream) {
     const dim3 grid = grid_for_groups(a.d, 1);
-    if (fast) nat_decode_kernel<true><<<grid, kBlock, 0, stream>>>(a);
-    else nat_decode_kernel<false><<<grid, kBlock, 0, stream>>>(a);
+    if (fast) nat_decode_kernel<<<grid, kBlock, 0, stream>>>(a);
+    else nat_decode_generic_kernel<<<grid, kBlock, 0, stream>>>(a);
     return hipGetLastError();
 }
 
 hipError_t launch_nat_aggregate(const NatAggregateArgs& a, bool fast, hipStream_t stream) {
     const dim3 grid = grid_for_groups(a.d, 1);
-    if (fast) nat_aggregate_kernel<true><<<grid, kBlock, 0, stream>>>(a);
-    else nat_aggregate_kernel<false><<<grid, kBlock, 0, stream>>>(a);
+    if (fast) nat_aggregate_kernel<<<grid, kBlock, 0, stream>>>(a);
+    else nat_aggregate_generic_kernel<<<grid, kBlock, 0, stream>>>(a);
     return hipGetLastError();
 }
 

@@ -65,8 +65,8 @@ nc_status nc_nat_encode_batch(const float* x, size_t x_stride, uint32_t n, uint6
     a.k0 = (uint32_t)seed; a.k1 = (uint32_t)(seed >> 32);
     a.first_worker = first_worker; a.index_offset = index_offset;
     a.exp_out = exp_out; a.exp_stride = exp_stride; a.sign_out = sign_out; a.sign_stride = sign_stride;
-    const bool fast = aligned(x, 16) && aligned(exp_out, 8) && (index_offset & 3) == 0 &&
-                      (n == 1 || ((x_stride & 3) == 0 && (exp_stride & 7) == 0));
+    const bool fast = aligned(x, 16) && aligned(exp_out, 4) && aligned(sign_out, 4) && (index_offset & 3) == 0 &&
+                      (n == 1 || ((x_stride & 3) == 0 && (exp_stride & 3) == 0 && (sign_stride & 3) == 0));
     return from_hip(launch_nat_encode(a, n, fast, (hipStream_t)stream));
 }
 
