@@ -113,7 +113,24 @@ __device__ __forceinline__ uint32_t bitfield_insert(uint32_t mask, uint32_t a, u
     return (a & mask) | (b & ~mask);
 }
 
+constexpr uint32_t kTileLanes = 256;  // lanes of the workgroups that use store_tile_transposed
+
 __device__ __forceinline__ uint32_t f32_bits(float f) { return __float_as_uint(f); }
 __device__ __forceinline__ float bits_f32(uint32_t u) { return __uint_as_float(u); }
+
+// Writes the workgroup's tile of results: lane t put its 8 values into LDS slots 2t, 2t+1;
+// now every lane stores slots t and t+256, i.e. 16 contiguous bytes per lane per instruction.
+// `groups` = number of whole groups of 8 in the tile (the others are not stored here).
+__device__ __forceinline__ void store_tile_transposed(u32x4* lds, const uint32_t v[8], bool have, uint32_t groups,
+                                                      float* __restrict__ out_tile) {
+    if (have) {
+        lds[2 * threadIdx.x] = u32x4{v[0], v[1], v[2], v[3]};
+        lds[2 * threadIdx.x + 1] = u32x4{v[4], v[5], v[6], v[7]};
+    }
+    __syncthreads();
+    u32x4* __restrict__ o = reinterpret_cast<u32x4*>(out_tile);
+    if (threadIdx.x < 2 * groups) store_stream(o + threadIdx.x, lds[threadIdx.x]);
+    if (threadIdx.x + kTileLanes < 2 * groups) store_stream(o + threadIdx.x + kTileLanes, lds[threadIdx.x + kTileLanes]);
+}
 
 }  // namespace natcomp

@@ -2,8 +2,12 @@
 // 0, 2^(1-s), ..., 1/2, 1): segment norms, encoder, and the decoder fused with the
 // n-worker sum (Algorithm 1's master sum; n = 1 is the plain decoder).
 //
-// As in the C_nat kernels one lane owns 8 consecutive elements, so it produces whole
-// bytes of every plane by itself (4 bytes of nibble codes or 8 code bytes, 1 sign byte).
+// Vector paths use the access shapes of the C_nat kernels: 16-byte lane-contiguous loads
+// (one quad = 4 elements = one Philox call per load), code halves and sign nibbles gathered
+// across neighbouring lanes with DPP row shifts so that stores are whole words, float
+// results transposed through LDS.  The scalar paths (any alignment, ragged tails, chunks
+// that straddle segment boundaries) let one lane own 8 consecutive elements, so it produces
+// whole bytes of every plane by itself.
 // Two encoders:
 //   - fixed buckets of <= 8192 elements: one workgroup per bucket keeps the bucket in
 //     registers, reduces the norm through LDS and encodes in the same pass, so x is read
@@ -102,6 +106,7 @@ __device__ __forceinline__ float inv_of_norm(float norm) {
 struct LevelParams {
     uint32_t s;
     int32_t e_min;        // 128 - s: smallest exponent field of y in the geometric region
+    int32_t e_max;        // 127: exponent field of y = 1, the top level
     uint32_t regular_lo;  // (128 - s) << 23: bits of the lowest non-zero level 2^(1-s)
     float low_scale;      // 2^(s+31): y * low_scale = threshold of the linear region (s <= 95)
 };
@@ -109,6 +114,7 @@ __device__ __forceinline__ LevelParams level_params(uint32_t s) {
     LevelParams p;
     p.s = s;
     p.e_min = 128 - (int32_t)s;
+    p.e_max = 127;
     p.regular_lo = (uint32_t)(128 - s) << 23;
     p.low_scale = (s <= 95) ? bits_f32((uint32_t)(127 + s + 31) << 23) : 0.0f;
     return p;
@@ -120,23 +126,24 @@ __device__ __forceinline__ LevelParams level_params(uint32_t s) {
 // and 0 otherwise; y >= 1 gives s.
 //
 // SMALL_S (s <= 95), branch-free: adding the 23 complemented top bits of r to y's bits
-// carries into the exponent field exactly when r < m 2^9; the exponent, rebased and
-// clamped to [0, s-1], is the code minus one in the geometric region and 0 below it.  The
-// last unit is "geometric region, or r < T" where T = floor(y 2^(s+31)) comes from one
-// multiply and a truncating conversion: one add-with-carry of T + rc + [geometric].
+// carries into the exponent field exactly when r < m 2^9; the exponent, clamped to
+// [128-s, 127] and rebased, is the code minus one in the geometric region and 0 below it.
+// The last unit is "geometric region, or r < T" where T = floor(y 2^(s+31)) comes from one
+// multiply and a truncating conversion, and r < T is the carry of T + ~r.
 template <bool SMALL_S>
 __device__ __forceinline__ uint32_t dither_level(float x, float inv, uint32_t rc, const LevelParams& lp) {
     const float y = fabsf(x) * inv;
     const uint32_t yb = f32_bits(y);
     if (SMALL_S) {
         const uint32_t bumped = yb + (rc >> 9);
-        const int32_t rebased = (int32_t)(bumped >> 23) - lp.e_min;
-        const uint32_t cm1 = (uint32_t)min(max(rebased, 0), (int32_t)lp.s - 1);  // v_med3_i32
+        int32_t e_clamped;  // exponent after the bump, clamped to [e_min, e_min + s - 1]
+        asm("v_med3_i32 %0, %1, %2, %3" : "=v"(e_clamped) : "v"(bumped >> 23), "v"(lp.e_min), "v"(lp.e_max));
         uint32_t T;
         asm("v_cvt_u32_f32 %0, %1" : "=v"(T) : "v"(y * lp.low_scale));  // truncates; saturates out of range
-        const uint32_t geometric = (yb >= lp.regular_lo) ? 1u : 0u;
-        const uint32_t plus = (uint32_t)(((uint64_t)T + rc + geometric) >> 32);
-        return cm1 + plus;
+        uint32_t unused;
+        const bool below = __builtin_uadd_overflow(T, rc, &unused);  // T + ~r carries  <=>  r < T
+        const bool geometric = yb >= lp.regular_lo;
+        return (uint32_t)(e_clamped - lp.e_min) + ((below || geometric) ? 1u : 0u);
     } else {
         const uint32_t ybm = yb & 0x7FFFFFFFu;
         const uint32_t r = ~rc;
@@ -236,6 +243,133 @@ __device__ __forceinline__ void encode_group(const DitherEncodeArgs& a, const ui
     store_codes8<FMT, FAST>(c, u, i0, count, a.code_out, a.sign_out);
 }
 
+// ------------------------------------------------------------------------ vector (quad) encode
+// Level codes of one quad with a common reciprocal norm.
+__device__ __forceinline__ void levels4(u32x4 v, float inv, const uint32_t rc[4], const LevelParams& lp,
+                                        uint32_t c[4]) {
+    if (lp.s <= 95) {
+        c[0] = dither_level<true>(bits_f32(v.x), inv, rc[0], lp);
+        c[1] = dither_level<true>(bits_f32(v.y), inv, rc[1], lp);
+        c[2] = dither_level<true>(bits_f32(v.z), inv, rc[2], lp);
+        c[3] = dither_level<true>(bits_f32(v.w), inv, rc[3], lp);
+    } else {
+        c[0] = dither_level<false>(bits_f32(v.x), inv, rc[0], lp);
+        c[1] = dither_level<false>(bits_f32(v.y), inv, rc[1], lp);
+        c[2] = dither_level<false>(bits_f32(v.z), inv, rc[2], lp);
+        c[3] = dither_level<false>(bits_f32(v.w), inv, rc[3], lp);
+    }
+}
+__device__ __forceinline__ uint32_t sign_nibble4(u32x4 v) {
+    uint32_t sg = v.w >> 31;
+    sg = push_sign(sg, v.z);
+    sg = push_sign(sg, v.y);
+    return push_sign(sg, v.x);
+}
+
+// Encodes quad q of the workgroup's tile and stores its codes; code_base / sign_base point
+// at the tile's first code / sign word (workgroup-uniform, so q stays a 32-bit offset) and
+// g_quad is the quad's global index in the random stream.  Must be called by all 64 lanes
+// of a wavefront with consecutive q (lane l holds q0 + l, q0 a multiple of 8); `in` says
+// whether the lane's quad exists and is the same for each run of 8 lanes.  Stores: nibble formats, one word of
+// 8 codes from every even lane; byte format, one word of 4 codes from every lane; sign
+// planes, one word of 32 sign bits from every 8th lane.
+template <int FMT>
+__device__ __forceinline__ void encode_store_quad(const DitherEncodeArgs& a, const LevelParams& lp, u32x4 v,
+                                                  float inv, uint32_t* __restrict__ code_base,
+                                                  uint32_t* __restrict__ sign_base, uint32_t q, uint64_t g_quad,
+                                                  bool in) {
+    uint32_t rc[4], c[4];
+    random_words4<true>(g_quad, a.worker, kDomainDither, a.k0, a.k1, rc);
+    levels4(v, inv, rc, lp, c);
+    if (FMT == kFmtByte) {
+        const uint32_t w = c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24);
+        if (in) store_stream(code_base + q, w);
+    } else {
+        uint32_t h = c[0] | (c[1] << 4) | (c[2] << 8) | (c[3] << 12);
+        if (FMT == kFmtFused)  // sign bit of element j to bit 4j+3
+            h |= ((v.x >> 28) & 0x8u) | ((v.y >> 24) & 0x80u) | ((v.z >> 20) & 0x800u) | ((v.w >> 16) & 0x8000u);
+        const uint32_t w = h | (from_lane_plus<1>(h) << 16);
+        if (in && (threadIdx.x & 1) == 0) store_stream(code_base + (q >> 1), w);
+    }
+    if (FMT != kFmtFused) {
+        const uint32_t packed = gather_nibbles8(sign_nibble4(v));
+        if (in && (threadIdx.x & 7) == 0) store_stream(sign_base + (q >> 3), packed);
+    }
+}
+
+template <int P>
+__device__ __forceinline__ void norm_add4_p(NormAcc& acc, u32x4 v) {
+    norm_add(acc, bits_f32(v.x), P);
+    norm_add(acc, bits_f32(v.y), P);
+    norm_add(acc, bits_f32(v.z), P);
+    norm_add(acc, bits_f32(v.w), P);
+}
+// Accumulates N quads; the switch on p is taken once, not per element.
+template <int N>
+__device__ __forceinline__ void norm_add_quads(NormAcc& acc, const u32x4 (&v)[N], int pnorm) {
+    if (pnorm == kNormInf) {
+#pragma unroll
+        for (int k = 0; k < N; ++k) norm_add4_p<kNormInf>(acc, v[k]);
+    } else if (pnorm == kNormL1) {
+#pragma unroll
+        for (int k = 0; k < N; ++k) norm_add4_p<kNormL1>(acc, v[k]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < N; ++k) norm_add4_p<kNormL2>(acc, v[k]);
+    }
+}
+
+// One-pass bucket encoder, vector path: bucket a multiple of 32 and at most 8192 elements,
+// x 16-byte aligned, code_out and sign_out 4-byte aligned, index_offset a multiple of 4.
+// One workgroup of 256 lanes per bucket; lane t owns quads t, t+256, ... (QPL of them),
+// all loaded before the norm is reduced, then encoded from registers.
+// (The register budget is capped for 6 wavefronts per SIMD: left alone, the scheduler
+// interleaves the QPL Philox chains and the kernel ends up with 2 wavefronts per SIMD.)
+template <int QPL, int FMT>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6, 8)))
+void dither_bucket_encode_vec_kernel(DitherEncodeArgs a) {
+    __shared__ NormAcc scratch[kBlock / 64];
+    const uint64_t begin = (uint64_t)blockIdx.x * a.segs.bucket;
+    const uint64_t rest = a.segs.d - begin;
+    const uint32_t len = rest < a.segs.bucket ? (uint32_t)rest : a.segs.bucket;
+    const uint32_t vec_quads = (len >> 5) << 3;  // quads inside whole groups of 32 elements
+    const u32x4* __restrict__ xv = reinterpret_cast<const u32x4*>(a.x + begin);
+    u32x4 v[QPL];
+#pragma unroll
+    for (int k = 0; k < QPL; ++k) {
+        const uint32_t q = threadIdx.x + k * kBlock;
+        v[k] = u32x4{0u, 0u, 0u, 0u};
+        if (q < vec_quads) v[k] = load_stream(xv + q);
+    }
+    NormAcc acc = norm_zero();
+    norm_add_quads(acc, v, a.pnorm);
+    const uint32_t tail0 = vec_quads * 4;  // the last bucket may end with up to 31 more elements
+    if (tail0 + threadIdx.x < len) norm_add(acc, a.x[begin + tail0 + threadIdx.x], a.pnorm);
+    acc = norm_block_reduce<kBlock>(acc, a.pnorm, scratch);
+    const float norm = norm_value(acc, a.pnorm);
+    if (threadIdx.x == 0) a.norms_out[blockIdx.x] = norm;
+    const float iv = inv_of_norm(norm);
+    const LevelParams lp = level_params(a.s);
+    const uint64_t q_global = (a.index_offset + begin) >> 2;
+    uint32_t* __restrict__ code_base = reinterpret_cast<uint32_t*>(a.code_out + (FMT == kFmtByte ? begin : begin >> 1));
+    uint32_t* __restrict__ sign_base = reinterpret_cast<uint32_t*>(a.sign_out + (begin >> 3));
+#pragma unroll
+    for (int k = 0; k < QPL; ++k) {
+        const uint32_t q = threadIdx.x + k * kBlock;
+        if (k * kBlock < vec_quads)  // block-uniform: skip rounds no lane takes part in
+            encode_store_quad<FMT>(a, lp, v[k], iv, code_base, sign_base, q, q_global + q, q < vec_quads);
+        __builtin_amdgcn_sched_barrier(0);  // one quad at a time keeps the register count low
+    }
+    if (tail0 < len && threadIdx.x < 4 && tail0 + threadIdx.x * 8 < len) {
+        const uint32_t l0 = tail0 + threadIdx.x * 8;
+        const uint32_t count = len - l0 < 8 ? len - l0 : 8u;
+        uint32_t u[8];
+        load8<false>(a.x, begin + l0, count, u);
+        const float inv[8] = {iv, iv, iv, iv, iv, iv, iv, iv};
+        encode_group<FMT, false>(a, u, inv, begin + l0, count);
+    }
+}
+
 // ------------------------------------------------------------------------ one-pass bucket encoder
 template <int BLOCK, int FMT, bool FAST>
 __global__ __launch_bounds__(BLOCK) void dither_bucket_encode_kernel(DitherEncodeArgs a) {
@@ -272,13 +406,24 @@ __global__ __launch_bounds__(kBlock) void dither_partial_kernel(DitherEncodeArgs
     const uint32_t s0 = seg_find(sg, cb);
     const uint32_t nseg = seg_count(sg);
     if (seg_end(sg, s0) >= ce) {  // the whole chunk lies in one segment
-        const uint64_t i0 = cb + (uint64_t)threadIdx.x * 8;
-        const uint32_t count = i0 >= ce ? 0u : (ce - i0 < 8 ? (uint32_t)(ce - i0) : 8u);
-        uint32_t u[8];
-        load8<FAST>(a.x, i0, count, u);
         NormAcc acc = norm_zero();
+        if (FAST) {  // lane-contiguous quads t and t+256 of the chunk, both loads issued first
+            const uint32_t len = (uint32_t)(ce - cb);
+            const uint32_t quads = len >> 2;
+            const u32x4* __restrict__ xv = reinterpret_cast<const u32x4*>(a.x + cb);
+            u32x4 v[2] = {u32x4{0u, 0u, 0u, 0u}, u32x4{0u, 0u, 0u, 0u}};
+            if (threadIdx.x < quads) v[0] = load_stream(xv + threadIdx.x);
+            if (threadIdx.x + kBlock < quads) v[1] = load_stream(xv + threadIdx.x + kBlock);
+            norm_add_quads(acc, v, a.pnorm);
+            if (quads * 4 + threadIdx.x < len) norm_add(acc, a.x[cb + quads * 4 + threadIdx.x], a.pnorm);
+        } else {
+            const uint64_t i0 = cb + (uint64_t)threadIdx.x * 8;
+            const uint32_t count = i0 >= ce ? 0u : (ce - i0 < 8 ? (uint32_t)(ce - i0) : 8u);
+            uint32_t u[8];
+            load8<false>(a.x, i0, count, u);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) norm_add(acc, bits_f32(u[j]), a.pnorm);
+            for (int j = 0; j < 8; ++j) norm_add(acc, bits_f32(u[j]), a.pnorm);
+        }
         acc = norm_block_reduce<kBlock>(acc, a.pnorm, scratch);
         if (threadIdx.x == 0) {
             const double v = a.pnorm == kNormInf ? (double)acc.mx : acc.sum;
@@ -329,20 +474,49 @@ __global__ __launch_bounds__(64) void dither_finalize_kernel(DitherEncodeArgs a)
     }
 }
 
-// Pass 3: encode with the finished norms.
+// Pass 3: encode with the finished norms.  A chunk that lies in one segment takes the
+// vector path (FAST: alignment as for the one-pass kernel); a chunk that straddles segment
+// boundaries, and the ragged end of the vector, go lane-by-lane in groups of 8.
 template <int FMT, bool FAST>
 __global__ __launch_bounds__(kBlock) void dither_segment_encode_kernel(DitherEncodeArgs a) {
     const Segs& sg = a.segs;
     const uint64_t cb = (uint64_t)blockIdx.x * kChunk;
     const uint64_t ce = cb + kChunk < sg.d ? cb + kChunk : sg.d;
-    const uint64_t i0 = cb + (uint64_t)threadIdx.x * 8;
+    const uint32_t s0 = seg_find(sg, cb);
+    const bool one_segment = seg_end(sg, s0) >= ce;  // block-uniform
+    uint32_t scalar_from = 0;                         // chunk-local element where the scalar part starts
+    if (FAST && one_segment) {
+        const uint32_t len = (uint32_t)(ce - cb);
+        const uint32_t vec_quads = (len >> 5) << 3;
+        const float iv = a.inv_norm[s0];
+        const LevelParams lp = level_params(a.s);
+        const u32x4* __restrict__ xv = reinterpret_cast<const u32x4*>(a.x + cb);
+        u32x4 v[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const uint32_t q = threadIdx.x + k * kBlock;
+            v[k] = u32x4{0u, 0u, 0u, 0u};
+            if (q < vec_quads) v[k] = load_stream(xv + q);
+        }
+        const uint64_t q_global = (a.index_offset + cb) >> 2;
+        uint32_t* __restrict__ code_base = reinterpret_cast<uint32_t*>(a.code_out + (FMT == kFmtByte ? cb : cb >> 1));
+        uint32_t* __restrict__ sign_base = reinterpret_cast<uint32_t*>(a.sign_out + (cb >> 3));
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const uint32_t q = threadIdx.x + k * kBlock;
+            if (k * kBlock < vec_quads)
+                encode_store_quad<FMT>(a, lp, v[k], iv, code_base, sign_base, q, q_global + q, q < vec_quads);
+        }
+        scalar_from = vec_quads * 4;
+        if (scalar_from >= len) return;
+    }
+    const uint64_t i0 = cb + scalar_from + (uint64_t)threadIdx.x * 8;
     if (i0 >= ce) return;
     const uint32_t count = ce - i0 < 8 ? (uint32_t)(ce - i0) : 8u;
     uint32_t u[8];
-    load8<FAST>(a.x, i0, count, u);
+    load8<false>(a.x, i0, count, u);
     float inv[8];
-    const uint32_t s0 = seg_find(sg, cb);
-    if (seg_end(sg, s0) >= ce) {
+    if (one_segment) {
         const float iv = a.inv_norm[s0];
 #pragma unroll
         for (int j = 0; j < 8; ++j) inv[j] = iv;
@@ -359,7 +533,7 @@ __global__ __launch_bounds__(kBlock) void dither_segment_encode_kernel(DitherEnc
             inv[j] = iv;
         }
     }
-    encode_group<FMT, FAST>(a, u, inv, i0, count);
+    encode_group<FMT, false>(a, u, inv, i0, count);
 }
 
 // ------------------------------------------------------------------------ decode and sum
@@ -370,28 +544,74 @@ __device__ __forceinline__ float dither_value(float norm, uint32_t s, uint32_t c
     return bits_f32(f32_bits(mag) | (sign_bit << 31));
 }
 
-// Table-driven fast path for the two nibble formats when a whole chunk lies in one segment:
-// for up to 16 workers at a time the workgroup tabulates in LDS the 16 possible values of a
-// nibble (fused format: sign included) and each element costs one bit-field extract, one
-// LDS read and one add per worker.
-template <int FMT, bool FAST>
+// NW workers starting at w: their code words (and sign bytes) are loaded first, then each of
+// the lane's 8 elements looks its value up in the workers' 16-entry tables and adds it.
+template <int FMT, int NW>
+__device__ __forceinline__ void dither_sum_chunk(const DitherAggregateArgs& a, const float* table, uint64_t grp,
+                                                 uint32_t w_table, size_t w_global, float acc[8]) {
+    uint32_t cw[NW], sb[NW];
+#pragma unroll
+    for (int k = 0; k < NW; ++k) {
+        cw[k] = load_stream(reinterpret_cast<const uint32_t*>(a.code + (w_global + k) * a.code_stride) + grp);
+        if (FMT == kFmtNibble) sb[k] = load_stream(a.sign + (w_global + k) * a.sign_stride + grp);
+    }
+#pragma unroll
+    for (int k = 0; k < NW; ++k) {
+        const float* row = table + (w_table + k) * 16;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float v = row[(cw[k] >> (4 * j)) & 15u];
+            if (FMT == kFmtNibble) v = bits_f32(f32_bits(v) | ((sb[k] << (31 - j)) & 0x80000000u));
+            acc[j] += v;
+        }
+    }
+}
+
+// One element of the sum by plain arithmetic (any layout and alignment).
+template <int FMT>
+__device__ __forceinline__ float dither_sum_one(const DitherAggregateArgs& a, uint64_t i, uint32_t seg) {
+    float acc = -0.0f;  // identity of binary32 addition: the sum starts from worker 0's value
+    for (uint32_t w = 0; w < a.n; ++w) {
+        const uint8_t* cp = a.code + (size_t)w * a.code_stride;
+        uint32_t c, sgn;
+        if (FMT == kFmtByte) {
+            c = cp[i];
+            sgn = (a.sign[(size_t)w * a.sign_stride + (i >> 3)] >> (i & 7)) & 1u;
+        } else {
+            const uint32_t nib = (cp[i >> 1] >> (4 * (i & 1))) & 15u;
+            if (FMT == kFmtFused) { c = nib & 7u; sgn = nib >> 3; }
+            else { c = nib; sgn = (a.sign[(size_t)w * a.sign_stride + (i >> 3)] >> (i & 7)) & 1u; }
+        }
+        acc += dither_value(a.norms[(size_t)w * a.norm_stride + seg], a.s, c, sgn);
+    }
+    return acc;
+}
+
+// Decode (n = 1) and fused decode-and-sum.  One lane owns 8 consecutive output elements;
+// results leave through the LDS transpose (VEC: out 16-byte aligned, code planes 4-byte
+// aligned with 4-byte-multiple strides).  Nibble formats in a chunk that lies inside one
+// segment use tables: for up to 16 workers at a time the workgroup tabulates in LDS the 16
+// values a nibble can decode to (fused format: sign included), so an element costs one
+// bit-field extract, one LDS read and one add per worker.  Everything else (byte codes,
+// chunks that straddle segments) is decoded arithmetically: norm * 2^(c-s).
+template <int FMT, bool VEC>
 __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregateArgs a) {
     __shared__ float table[16 * 16];
+    __shared__ u32x4 tile[2 * kBlock];
     const Segs& sg = a.segs;
     const uint64_t cb = (uint64_t)blockIdx.x * kChunk;
     const uint64_t ce = cb + kChunk < sg.d ? cb + kChunk : sg.d;
-    const uint64_t i0 = cb + (uint64_t)threadIdx.x * 8;
+    const uint64_t grp = (cb >> 3) + threadIdx.x;
+    const uint64_t i0 = grp * 8;
     const uint32_t count = i0 >= ce ? 0u : (ce - i0 < 8 ? (uint32_t)(ce - i0) : 8u);
     const uint32_t s0 = seg_find(sg, cb);
     const bool one_segment = seg_end(sg, s0) >= ce;
-    float acc[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+    float acc[8] = {-0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f};
 
-    if (FMT != kFmtByte && one_segment) {
+    if (VEC && FMT != kFmtByte && one_segment) {
         for (uint32_t w0 = 0; w0 < a.n; w0 += 16) {
             const uint32_t nw = a.n - w0 < 16 ? a.n - w0 : 16u;
-            {   // tabulate: entry (w, nibble)
+            {   // tabulate: entry (worker, nibble)
                 const uint32_t w = threadIdx.x >> 4, nib = threadIdx.x & 15u;
                 if (w < nw) {
                     const float norm = a.norms[(size_t)(w0 + w) * a.norm_stride + s0];
@@ -400,78 +620,48 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
                 }
             }
             __syncthreads();
-            if (count) {
-                for (uint32_t w = 0; w < nw; w += 8) {
-                    uint32_t cw[8], sb[8];
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        if (w + k < nw) {
-                            const size_t ww = w0 + w + k;
-                            const uint8_t* cp = a.code + ww * a.code_stride + (i0 >> 1);
-                            if (FAST && count == 8) {
-                                cw[k] = load_stream(reinterpret_cast<const uint32_t*>(cp));
-                            } else {
-                                cw[k] = 0;
-                                for (uint32_t b = 0; b < (count + 1) >> 1; ++b) cw[k] |= (uint32_t)cp[b] << (8 * b);
-                            }
-                            if (FMT == kFmtNibble) sb[k] = a.sign[ww * a.sign_stride + (i0 >> 3)];
-                        }
-                    }
-#pragma unroll
-                    for (int k = 0; k < 8; ++k) {
-                        if (w + k < nw) {
-                            const float* row = table + (w + k) * 16;
-#pragma unroll
-                            for (int j = 0; j < 8; ++j) {
-                                float v = row[(cw[k] >> (4 * j)) & 15u];
-                                if (FMT == kFmtNibble) v = bits_f32(f32_bits(v) | ((sb[k] << (31 - j)) & 0x80000000u));
-                                acc[j] = (w0 + w + k == 0) ? v : acc[j] + v;
-                            }
-                        }
-                    }
+            if (count == 8) {
+                uint32_t w = 0;
+                for (; w + 8 <= nw; w += 8) dither_sum_chunk<FMT, 8>(a, table, grp, w, w0 + w, acc);
+                switch (nw - w) {
+                    case 1: dither_sum_chunk<FMT, 1>(a, table, grp, w, w0 + w, acc); break;
+                    case 2: dither_sum_chunk<FMT, 2>(a, table, grp, w, w0 + w, acc); break;
+                    case 3: dither_sum_chunk<FMT, 3>(a, table, grp, w, w0 + w, acc); break;
+                    case 4: dither_sum_chunk<FMT, 4>(a, table, grp, w, w0 + w, acc); break;
+                    case 5: dither_sum_chunk<FMT, 5>(a, table, grp, w, w0 + w, acc); break;
+                    case 6: dither_sum_chunk<FMT, 6>(a, table, grp, w, w0 + w, acc); break;
+                    case 7: dither_sum_chunk<FMT, 7>(a, table, grp, w, w0 + w, acc); break;
+                    default: break;
                 }
             }
             __syncthreads();
         }
-    } else if (count) {
-        // any layout: walk the segments element by element
-        uint32_t seg[8];
-        {
-            const uint32_t last = seg_count(sg) - 1;
-            uint32_t s = seg_find(sg, i0);
-            uint64_t se = seg_end(sg, s);
+        if (count > 0 && count < 8) {  // the ragged last group of the vector
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if ((uint32_t)j < count) {
-                    while (i0 + j >= se && s < last) { ++s; se = seg_end(sg, s); }
-                }
-                seg[j] = s;
-            }
+            for (int j = 0; j < 8; ++j) if ((uint32_t)j < count) acc[j] = dither_sum_one<FMT>(a, i0 + j, s0);
         }
-        for (uint32_t w = 0; w < a.n; ++w) {
-            const uint8_t* cp = a.code + (size_t)w * a.code_stride;
-            const uint32_t sbyte = (FMT == kFmtFused) ? 0u : a.sign[(size_t)w * a.sign_stride + (i0 >> 3)];
-            const float* nr = a.norms + (size_t)w * a.norm_stride;
+    } else if (count) {
+        const uint32_t last = seg_count(sg) - 1;
+        uint32_t s = one_segment ? s0 : seg_find(sg, i0);
+        uint64_t se = seg_end(sg, s);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if ((uint32_t)j < count) {
-                    uint32_t c, sgn;
-                    if (FMT == kFmtByte) {
-                        c = cp[i0 + j]; sgn = (sbyte >> j) & 1u;
-                    } else {
-                        const uint32_t nib = (cp[(i0 + j) >> 1] >> (4 * (j & 1))) & 15u;
-                        if (FMT == kFmtFused) { c = nib & 7u; sgn = nib >> 3; } else { c = nib; sgn = (sbyte >> j) & 1u; }
-                    }
-                    const float v = dither_value(nr[seg[j]], a.s, c, sgn);
-                    acc[j] = (w == 0) ? v : acc[j] + v;
-                }
+        for (int j = 0; j < 8; ++j) {
+            if ((uint32_t)j < count) {
+                while (i0 + j >= se && s < last) { ++s; se = seg_end(sg, s); }
+                acc[j] = dither_sum_one<FMT>(a, i0 + j, s);
             }
         }
     }
-    if (count == 8 && FAST) {
-        u32x4* o = reinterpret_cast<u32x4*>(a.out + i0);
-        store_stream(o, u32x4{f32_bits(acc[0]), f32_bits(acc[1]), f32_bits(acc[2]), f32_bits(acc[3])});
-        store_stream(o + 1, u32x4{f32_bits(acc[4]), f32_bits(acc[5]), f32_bits(acc[6]), f32_bits(acc[7])});
+    if (VEC) {
+        uint32_t bits[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) bits[j] = f32_bits(acc[j]);
+        const uint32_t groups = (uint32_t)((ce - cb) >> 3);  // whole groups of 8 in this chunk
+        store_tile_transposed(tile, bits, count == 8, groups, a.out + cb);
+        if (count > 0 && count < 8) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) if ((uint32_t)j < count) a.out[i0 + j] = acc[j];
+        }
     } else {
 #pragma unroll
         for (int j = 0; j < 8; ++j) if ((uint32_t)j < count) a.out[i0 + j] = acc[j];
@@ -489,8 +679,25 @@ static hipError_t launch_bucket(const DitherEncodeArgs& a, unsigned grid, hipStr
     return hipGetLastError();
 }
 
+template <int QPL>
+static hipError_t launch_bucket_vec(const DitherEncodeArgs& a, unsigned grid, hipStream_t st) {
+    switch (a.fmt) {
+        case kFmtFused: dither_bucket_encode_vec_kernel<QPL, kFmtFused><<<grid, kBlock, 0, st>>>(a); break;
+        case kFmtNibble: dither_bucket_encode_vec_kernel<QPL, kFmtNibble><<<grid, kBlock, 0, st>>>(a); break;
+        default: dither_bucket_encode_vec_kernel<QPL, kFmtByte><<<grid, kBlock, 0, st>>>(a); break;
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_dither_bucket_encode(const DitherEncodeArgs& a, bool fast, hipStream_t stream) {
     const unsigned grid = (unsigned)((a.segs.d + a.segs.bucket - 1) / a.segs.bucket);
+    if (fast && (a.segs.bucket & 31) == 0) {  // vector path: 256 lanes, QPL quads per lane
+        const uint32_t quads = a.segs.bucket / 4;
+        if (quads <= 256) return launch_bucket_vec<1>(a, grid, stream);
+        if (quads <= 512) return launch_bucket_vec<2>(a, grid, stream);
+        if (quads <= 1024) return launch_bucket_vec<4>(a, grid, stream);
+        return launch_bucket_vec<8>(a, grid, stream);
+    }
     const uint32_t lanes = (a.segs.bucket + 7) / 8;
     if (lanes <= 256) return fast ? launch_bucket<256, true>(a, grid, stream) : launch_bucket<256, false>(a, grid, stream);
     if (lanes <= 512) return fast ? launch_bucket<512, true>(a, grid, stream) : launch_bucket<512, false>(a, grid, stream);

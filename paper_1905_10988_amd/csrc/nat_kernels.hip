@@ -140,21 +140,6 @@ __device__ __forceinline__ void nat_decode8(u32x2 e, uint32_t sb, uint32_t v[8])
     v[7] = bitfield_insert(kExpMask, e.y >> 1, sb << 24);
 }
 
-// Writes the workgroup's tile of results: lane t put its 8 values into LDS slots 2t, 2t+1;
-// now every lane stores slots t and t+256, i.e. 16 contiguous bytes per lane per instruction.
-// `groups` = number of whole groups of 8 in the tile (the others are not stored here).
-__device__ __forceinline__ void store_tile_transposed(u32x4* lds, const uint32_t v[8], bool have, uint32_t groups,
-                                                      float* __restrict__ out_tile) {
-    if (have) {
-        lds[2 * threadIdx.x] = u32x4{v[0], v[1], v[2], v[3]};
-        lds[2 * threadIdx.x + 1] = u32x4{v[4], v[5], v[6], v[7]};
-    }
-    __syncthreads();
-    u32x4* __restrict__ o = reinterpret_cast<u32x4*>(out_tile);
-    if (threadIdx.x < 2 * groups) store_stream(o + threadIdx.x, lds[threadIdx.x]);
-    if (threadIdx.x + kBlock < 2 * groups) store_stream(o + threadIdx.x + kBlock, lds[threadIdx.x + kBlock]);
-}
-
 // Vector decoder.  Requires exp 8-byte aligned and out 16-byte aligned.
 __global__ __launch_bounds__(kBlock) void nat_decode_kernel(NatDecodeArgs a) {
     __shared__ u32x4 lds[2 * kBlock];

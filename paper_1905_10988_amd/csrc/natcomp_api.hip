@@ -135,7 +135,8 @@ nc_status nc_dither_encode(const float* x, uint64_t d, const uint64_t* seg_offse
     a.x = x; a.pnorm = pnorm; a.s = s; a.fmt = fmt;
     a.k0 = (uint32_t)seed; a.k1 = (uint32_t)(seed >> 32); a.worker = worker; a.index_offset = index_offset;
     a.norms_out = norms_out; a.code_out = code_out; a.sign_out = sign_out;
-    const bool fast = aligned(x, 16) && (index_offset & 3) == 0 && aligned(code_out, fmt == kFmtByte ? 8 : 4);
+    const bool fast = aligned(x, 16) && (index_offset & 3) == 0 && aligned(code_out, fmt == kFmtByte ? 8 : 4) &&
+                      (fmt == kFmtFused || aligned(sign_out, 4));
     if (one_pass_bucket(seg_offsets, bucket))
         return from_hip(launch_dither_bucket_encode(a, fast, (hipStream_t)stream));
     const size_t need = nc_dither_workspace_bytes(d, num_segments, bucket, seg_offsets != nullptr);
@@ -167,8 +168,7 @@ static nc_status dither_aggregate(const float* norms, size_t norm_stride, const 
     }
     a.norms = norms; a.norm_stride = norm_stride; a.code = code; a.code_stride = code_stride;
     a.sign = sign; a.sign_stride = sign_stride; a.n = n; a.s = s; a.fmt = fmt; a.out = out;
-    const size_t ca = fmt == kFmtByte ? 8 : 4;
-    const bool fast = aligned(code, ca) && aligned(out, 16) && (n == 1 || (code_stride & (ca - 1)) == 0);
+    const bool fast = aligned(code, 4) && aligned(out, 16) && (n == 1 || (code_stride & 3) == 0);
     return from_hip(launch_dither_aggregate(a, fast, (hipStream_t)stream));
 }
 
