@@ -32,6 +32,21 @@ __device__ __forceinline__ uint32_t seg_find(const Segs& sg, uint64_t i) {
     }
     return sg.bucket ? (uint32_t)(i / sg.bucket) : 0u;
 }
+// The same answer for a workgroup-uniform position, found by the whole workgroup: with at
+// most kBlock segments one round of loads (lane t tests segment t) replaces the dependent
+// chain of a binary search.  `slot` is one LDS word; all lanes must call.
+__device__ __forceinline__ uint32_t seg_find_block(const Segs& sg, uint64_t i, uint32_t* slot) {
+    if (!sg.offsets) return sg.bucket ? (uint32_t)(i / sg.bucket) : 0u;
+    if (sg.num_segments > (uint32_t)kBlock || blockDim.x != (unsigned)kBlock) return seg_find(sg, i);
+    if (threadIdx.x == 0) *slot = 0;
+    __syncthreads();
+    if (threadIdx.x < sg.num_segments) {
+        const uint64_t b = sg.offsets[threadIdx.x], e = sg.offsets[threadIdx.x + 1];
+        if (b <= i && i < e) *slot = threadIdx.x;  // at most one non-empty segment holds i
+    }
+    __syncthreads();
+    return *slot;
+}
 __device__ __forceinline__ uint64_t seg_begin(const Segs& sg, uint32_t s) {
     if (sg.offsets) return sg.offsets[s];
     return sg.bucket ? (uint64_t)s * sg.bucket : 0ull;
@@ -65,12 +80,12 @@ __device__ __forceinline__ NormAcc norm_merge(NormAcc a, NormAcc b, int pnorm) {
 }
 // Butterfly over the 64 lanes: every lane ends with the same bits.
 __device__ __forceinline__ NormAcc norm_wave_reduce(NormAcc a, int pnorm) {
+    if (pnorm == kNormInf) {
 #pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-        NormAcc o;
-        o.sum = __shfl_xor(a.sum, m, 64);
-        o.mx = __shfl_xor(a.mx, m, 64);
-        a = norm_merge(a, o, pnorm);
+        for (int m = 32; m >= 1; m >>= 1) a.mx = fmaxf(a.mx, __shfl_xor(a.mx, m, 64));
+    } else {
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) a.sum += __shfl_xor(a.sum, m, 64);
     }
     return a;
 }
@@ -394,40 +409,41 @@ __global__ __launch_bounds__(BLOCK) void dither_bucket_encode_kernel(DitherEncod
 }
 
 // ------------------------------------------------------------------------ two-pass path
-// Pass 1: partial norm of every (segment, chunk) intersection.  The piece of the segment
-// that continues into a chunk from the left goes to first_partial[chunk]; a segment that
-// starts inside the chunk puts its first piece into head_partial[segment].
+// Pass 1: partial norm of every (segment, chunk) intersection, chunks of kNormChunk
+// elements.  The piece of the segment that continues into a chunk from the left goes to
+// first_partial[chunk]; a segment that starts inside the chunk puts its first piece into
+// head_partial[segment].  FAST: lane t holds quads t, t+256, ... of the chunk, all loaded
+// before the segment search; a chunk that straddles segments is reduced piece by piece from
+// the same registers.
 template <bool FAST>
 __global__ __launch_bounds__(kBlock) void dither_partial_kernel(DitherEncodeArgs a) {
     __shared__ NormAcc scratch[kBlock / 64];
+    __shared__ uint32_t slot;
+    constexpr int kQuads = kNormChunk / 4 / kBlock;  // quads per lane
     const Segs& sg = a.segs;
-    const uint64_t cb = (uint64_t)blockIdx.x * kChunk;
-    const uint64_t ce = cb + kChunk < sg.d ? cb + kChunk : sg.d;
-    const uint32_t s0 = seg_find(sg, cb);
-    const uint32_t nseg = seg_count(sg);
-    if (seg_end(sg, s0) >= ce) {  // the whole chunk lies in one segment
-        NormAcc acc = norm_zero();
-        if (FAST) {  // lane-contiguous quads t and t+256 of the chunk, both loads issued first
-            const uint32_t len = (uint32_t)(ce - cb);
-            const uint32_t quads = len >> 2;
-            const u32x4* __restrict__ xv = reinterpret_cast<const u32x4*>(a.x + cb);
-            u32x4 v[2] = {u32x4{0u, 0u, 0u, 0u}, u32x4{0u, 0u, 0u, 0u}};
-            if (threadIdx.x < quads) v[0] = load_stream(xv + threadIdx.x);
-            if (threadIdx.x + kBlock < quads) v[1] = load_stream(xv + threadIdx.x + kBlock);
-            norm_add_quads(acc, v, a.pnorm);
-            if (quads * 4 + threadIdx.x < len) norm_add(acc, a.x[cb + quads * 4 + threadIdx.x], a.pnorm);
-        } else {
-            const uint64_t i0 = cb + (uint64_t)threadIdx.x * 8;
-            const uint32_t count = i0 >= ce ? 0u : (ce - i0 < 8 ? (uint32_t)(ce - i0) : 8u);
-            uint32_t u[8];
-            load8<false>(a.x, i0, count, u);
+    const uint64_t cb = (uint64_t)blockIdx.x * kNormChunk;
+    const uint64_t ce = cb + kNormChunk < sg.d ? cb + kNormChunk : sg.d;
+    const bool vec = FAST && (ce - cb) == kNormChunk;  // a whole chunk: unconditional vector loads
+    u32x4 v[kQuads];
+    if (vec) {
+        const u32x4* __restrict__ xv = reinterpret_cast<const u32x4*>(a.x + cb) + threadIdx.x;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) norm_add(acc, bits_f32(u[j]), a.pnorm);
-        }
+        for (int k = 0; k < kQuads; ++k) v[k] = load_stream(xv + k * kBlock);
+    }
+    const uint32_t s0 = seg_find_block(sg, cb, &slot);
+    const uint32_t nseg = seg_count(sg);
+    if (vec) {  // keep the loaded values opaque up to here, so that nothing is computed from
+                // them (and held in registers) ahead of the search
+#pragma unroll
+        for (int k = 0; k < kQuads; ++k) asm volatile("" : "+v"(v[k]));
+    }
+    if (vec && seg_end(sg, s0) >= ce) {  // the whole chunk lies in one segment
+        NormAcc acc = norm_zero();
+        norm_add_quads(acc, v, a.pnorm);
         acc = norm_block_reduce<kBlock>(acc, a.pnorm, scratch);
         if (threadIdx.x == 0) {
-            const double v = a.pnorm == kNormInf ? (double)acc.mx : acc.sum;
-            if (seg_begin(sg, s0) >= cb) a.head_partial[s0] = v; else a.first_partial[blockIdx.x] = v;
+            const double r = a.pnorm == kNormInf ? (double)acc.mx : acc.sum;
+            if (seg_begin(sg, s0) >= cb) a.head_partial[s0] = r; else a.first_partial[blockIdx.x] = r;
         }
         return;
     }
@@ -437,36 +453,51 @@ __global__ __launch_bounds__(kBlock) void dither_partial_kernel(DitherEncodeArgs
         const uint64_t b = sb > cb ? sb : cb, e = se < ce ? se : ce;
         if (e <= b) continue;  // empty segment
         NormAcc acc = norm_zero();
-        for (uint64_t i = b + threadIdx.x; i < e; i += kBlock) norm_add(acc, a.x[i], a.pnorm);
+        if (vec) {
+            const uint32_t lb = (uint32_t)(b - cb), span = (uint32_t)(e - b);  // chunk-local piece
+            u32x4 m[kQuads];  // the lane's values inside the piece, zeros elsewhere (zeros add nothing)
+#pragma unroll
+            for (int k = 0; k < kQuads; ++k) {
+                const uint32_t l0 = (threadIdx.x + k * kBlock) * 4;
+                m[k].x = (l0 + 0 - lb < span) ? v[k].x : 0u;
+                m[k].y = (l0 + 1 - lb < span) ? v[k].y : 0u;
+                m[k].z = (l0 + 2 - lb < span) ? v[k].z : 0u;
+                m[k].w = (l0 + 3 - lb < span) ? v[k].w : 0u;
+            }
+            norm_add_quads(acc, m, a.pnorm);
+        } else {
+            for (uint64_t i = b + threadIdx.x; i < e; i += kBlock) norm_add(acc, a.x[i], a.pnorm);
+        }
         acc = norm_block_reduce<kBlock>(acc, a.pnorm, scratch);
         if (threadIdx.x == 0) {
-            const double v = a.pnorm == kNormInf ? (double)acc.mx : acc.sum;
-            if (sb >= cb) a.head_partial[s] = v; else a.first_partial[blockIdx.x] = v;
+            const double r = a.pnorm == kNormInf ? (double)acc.mx : acc.sum;
+            if (sb >= cb) a.head_partial[s] = r; else a.first_partial[blockIdx.x] = r;
         }
     }
 }
 
-// Pass 2: one wavefront per segment adds the segment's partials in a fixed order.
-__global__ __launch_bounds__(64) void dither_finalize_kernel(DitherEncodeArgs a) {
+// Pass 2: one workgroup per segment adds the segment's partials in a fixed order.
+__global__ __launch_bounds__(kBlock) void dither_finalize_kernel(DitherEncodeArgs a) {
+    __shared__ NormAcc scratch[kBlock / 64];
     const Segs& sg = a.segs;
     const uint32_t s = blockIdx.x;
     const uint64_t b = seg_begin(sg, s), e = seg_end(sg, s);
     NormAcc acc = norm_zero();
     if (e > b) {
-        const uint64_t c_head = b / kChunk, c_last = (e - 1) / kChunk;
+        const uint64_t c_head = b / kNormChunk, c_last = (e - 1) / kNormChunk;
         // the piece in the chunk where the segment starts is in head_partial
         if (threadIdx.x == 0) {
-            const double v = a.head_partial[s];
-            if (a.pnorm == kNormInf) acc.mx = (float)v; else acc.sum = v;
+            const double r = a.head_partial[s];
+            if (a.pnorm == kNormInf) acc.mx = (float)r; else acc.sum = r;
         }
-        for (uint64_t c = c_head + 1 + threadIdx.x; c <= c_last; c += 64) {
-            const double v = a.first_partial[c];
+        for (uint64_t c = c_head + 1 + threadIdx.x; c <= c_last; c += kBlock) {
+            const double r = a.first_partial[c];
             NormAcc o = norm_zero();
-            if (a.pnorm == kNormInf) o.mx = (float)v; else o.sum = v;
+            if (a.pnorm == kNormInf) o.mx = (float)r; else o.sum = r;
             acc = norm_merge(acc, o, a.pnorm);
         }
     }
-    acc = norm_wave_reduce(acc, a.pnorm);
+    acc = norm_block_reduce<kBlock>(acc, a.pnorm, scratch);
     if (threadIdx.x == 0) {
         const float norm = norm_value(acc, a.pnorm);
         a.norms_out[s] = norm;
@@ -479,25 +510,28 @@ __global__ __launch_bounds__(64) void dither_finalize_kernel(DitherEncodeArgs a)
 // boundaries, and the ragged end of the vector, go lane-by-lane in groups of 8.
 template <int FMT, bool FAST>
 __global__ __launch_bounds__(kBlock) void dither_segment_encode_kernel(DitherEncodeArgs a) {
+    __shared__ uint32_t slot;
     const Segs& sg = a.segs;
     const uint64_t cb = (uint64_t)blockIdx.x * kChunk;
     const uint64_t ce = cb + kChunk < sg.d ? cb + kChunk : sg.d;
-    const uint32_t s0 = seg_find(sg, cb);
-    const bool one_segment = seg_end(sg, s0) >= ce;  // block-uniform
-    uint32_t scalar_from = 0;                         // chunk-local element where the scalar part starts
-    if (FAST && one_segment) {
-        const uint32_t len = (uint32_t)(ce - cb);
-        const uint32_t vec_quads = (len >> 5) << 3;
-        const float iv = a.inv_norm[s0];
-        const LevelParams lp = level_params(a.s);
+    const uint32_t len = (uint32_t)(ce - cb);
+    const uint32_t vec_quads = (len >> 5) << 3;
+    u32x4 v[2];
+    if (FAST) {  // the loads do not depend on the segment: issue them before the search
         const u32x4* __restrict__ xv = reinterpret_cast<const u32x4*>(a.x + cb);
-        u32x4 v[2];
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
             const uint32_t q = threadIdx.x + k * kBlock;
             v[k] = u32x4{0u, 0u, 0u, 0u};
             if (q < vec_quads) v[k] = load_stream(xv + q);
         }
+    }
+    const uint32_t s0 = seg_find_block(sg, cb, &slot);
+    const bool one_segment = seg_end(sg, s0) >= ce;  // block-uniform
+    uint32_t scalar_from = 0;                         // chunk-local element where the scalar part starts
+    if (FAST && one_segment) {
+        const float iv = a.inv_norm[s0];
+        const LevelParams lp = level_params(a.s);
         const uint64_t q_global = (a.index_offset + cb) >> 2;
         uint32_t* __restrict__ code_base = reinterpret_cast<uint32_t*>(a.code_out + (FMT == kFmtByte ? cb : cb >> 1));
         uint32_t* __restrict__ sign_base = reinterpret_cast<uint32_t*>(a.sign_out + (cb >> 3));
@@ -544,17 +578,20 @@ __device__ __forceinline__ float dither_value(float norm, uint32_t s, uint32_t c
     return bits_f32(f32_bits(mag) | (sign_bit << 31));
 }
 
-// NW workers starting at w: their code words (and sign bytes) are loaded first, then each of
-// the lane's 8 elements looks its value up in the workers' 16-entry tables and adds it.
+// Code words (8 nibbles) and sign bytes of the lane's group for NW workers starting at w.
 template <int FMT, int NW>
-__device__ __forceinline__ void dither_sum_chunk(const DitherAggregateArgs& a, const float* table, uint64_t grp,
-                                                 uint32_t w_table, size_t w_global, float acc[8]) {
-    uint32_t cw[NW], sb[NW];
+__device__ __forceinline__ void dither_load_codes(const DitherAggregateArgs& a, uint64_t grp, size_t w,
+                                                  uint32_t cw[NW], uint32_t sb[NW]) {
 #pragma unroll
     for (int k = 0; k < NW; ++k) {
-        cw[k] = load_stream(reinterpret_cast<const uint32_t*>(a.code + (w_global + k) * a.code_stride) + grp);
-        if (FMT == kFmtNibble) sb[k] = load_stream(a.sign + (w_global + k) * a.sign_stride + grp);
+        cw[k] = load_stream(reinterpret_cast<const uint32_t*>(a.code + (w + k) * a.code_stride) + grp);
+        sb[k] = (FMT == kFmtNibble) ? (uint32_t)load_stream(a.sign + (w + k) * a.sign_stride + grp) : 0u;
     }
+}
+// Each of the lane's 8 elements looks its value up in the workers' 16-entry tables and adds it.
+template <int FMT, int NW>
+__device__ __forceinline__ void dither_add_codes(const float* table, uint32_t w_table, const uint32_t cw[NW],
+                                                 const uint32_t sb[NW], float acc[8]) {
 #pragma unroll
     for (int k = 0; k < NW; ++k) {
         const float* row = table + (w_table + k) * 16;
@@ -565,6 +602,13 @@ __device__ __forceinline__ void dither_sum_chunk(const DitherAggregateArgs& a, c
             acc[j] += v;
         }
     }
+}
+template <int FMT, int NW>
+__device__ __forceinline__ void dither_sum_chunk(const DitherAggregateArgs& a, const float* table, uint64_t grp,
+                                                 uint32_t w_table, size_t w_global, float acc[8]) {
+    uint32_t cw[NW], sb[NW];
+    dither_load_codes<FMT, NW>(a, grp, w_global, cw, sb);
+    dither_add_codes<FMT, NW>(table, w_table, cw, sb, acc);
 }
 
 // One element of the sum by plain arithmetic (any layout and alignment).
@@ -598,17 +642,27 @@ template <int FMT, bool VEC>
 __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregateArgs a) {
     __shared__ float table[16 * 16];
     __shared__ u32x4 tile[2 * kBlock];
+    __shared__ uint32_t slot;
     const Segs& sg = a.segs;
     const uint64_t cb = (uint64_t)blockIdx.x * kChunk;
     const uint64_t ce = cb + kChunk < sg.d ? cb + kChunk : sg.d;
     const uint64_t grp = (cb >> 3) + threadIdx.x;
     const uint64_t i0 = grp * 8;
     const uint32_t count = i0 >= ce ? 0u : (ce - i0 < 8 ? (uint32_t)(ce - i0) : 8u);
-    const uint32_t s0 = seg_find(sg, cb);
+    // The first (up to 8) workers' codes do not depend on the segment: load them before the
+    // segment search and the table, so the two global round trips overlap.
+    constexpr bool kTables = VEC && FMT != kFmtByte;
+    const uint32_t n_first = a.n >= 8 ? 8u : (a.n == 1 ? 1u : 0u);  // 2..7 workers: no preload
+    uint32_t cw0[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u}, sb0[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+    if (kTables && count == 8) {
+        if (n_first == 8) dither_load_codes<FMT, 8>(a, grp, 0, cw0, sb0);
+        else if (n_first == 1) dither_load_codes<FMT, 1>(a, grp, 0, cw0, sb0);
+    }
+    const uint32_t s0 = seg_find_block(sg, cb, &slot);
     const bool one_segment = seg_end(sg, s0) >= ce;
     float acc[8] = {-0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f};
 
-    if (VEC && FMT != kFmtByte && one_segment) {
+    if (kTables && one_segment) {
         for (uint32_t w0 = 0; w0 < a.n; w0 += 16) {
             const uint32_t nw = a.n - w0 < 16 ? a.n - w0 : 16u;
             {   // tabulate: entry (worker, nibble)
@@ -622,17 +676,18 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
             __syncthreads();
             if (count == 8) {
                 uint32_t w = 0;
-                for (; w + 8 <= nw; w += 8) dither_sum_chunk<FMT, 8>(a, table, grp, w, w0 + w, acc);
-                switch (nw - w) {
-                    case 1: dither_sum_chunk<FMT, 1>(a, table, grp, w, w0 + w, acc); break;
-                    case 2: dither_sum_chunk<FMT, 2>(a, table, grp, w, w0 + w, acc); break;
-                    case 3: dither_sum_chunk<FMT, 3>(a, table, grp, w, w0 + w, acc); break;
-                    case 4: dither_sum_chunk<FMT, 4>(a, table, grp, w, w0 + w, acc); break;
-                    case 5: dither_sum_chunk<FMT, 5>(a, table, grp, w, w0 + w, acc); break;
-                    case 6: dither_sum_chunk<FMT, 6>(a, table, grp, w, w0 + w, acc); break;
-                    case 7: dither_sum_chunk<FMT, 7>(a, table, grp, w, w0 + w, acc); break;
-                    default: break;
+                if (w0 == 0) {  // the preloaded workers
+                    // keep the code words opaque up to here: otherwise all 64 table addresses are
+                    // computed ahead of the barrier and the kernel loses half its wavefronts
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) asm volatile("" : "+v"(cw0[k]), "+v"(sb0[k]));
+                    if (n_first == 8) dither_add_codes<FMT, 8>(table, 0, cw0, sb0, acc);
+                    else if (n_first == 1) dither_add_codes<FMT, 1>(table, 0, cw0, sb0, acc);
+                    w = n_first;
                 }
+                for (; w + 8 <= nw; w += 8) dither_sum_chunk<FMT, 8>(a, table, grp, w, w0 + w, acc);
+                for (; w + 2 <= nw; w += 2) dither_sum_chunk<FMT, 2>(a, table, grp, w, w0 + w, acc);
+                if (w < nw) dither_sum_chunk<FMT, 1>(a, table, grp, w, w0 + w, acc);
             }
             __syncthreads();
         }
@@ -707,12 +762,13 @@ hipError_t launch_dither_bucket_encode(const DitherEncodeArgs& a, bool fast, hip
 template <bool FAST>
 static hipError_t launch_segment(const DitherEncodeArgs& a, hipStream_t st) {
     const unsigned chunks = (unsigned)((a.segs.d + kChunk - 1) / kChunk);
+    const unsigned norm_chunks = (unsigned)((a.segs.d + kNormChunk - 1) / kNormChunk);
     const unsigned nseg = (unsigned)(a.segs.offsets ? a.segs.num_segments
                                      : a.segs.bucket ? (a.segs.d + a.segs.bucket - 1) / a.segs.bucket : 1);
-    dither_partial_kernel<FAST><<<chunks, kBlock, 0, st>>>(a);
+    dither_partial_kernel<FAST><<<norm_chunks, kBlock, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    dither_finalize_kernel<<<nseg, 64, 0, st>>>(a);
+    dither_finalize_kernel<<<nseg, kBlock, 0, st>>>(a);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     switch (a.fmt) {

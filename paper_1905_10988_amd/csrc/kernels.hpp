@@ -36,6 +36,7 @@ enum { kNormL1 = 1, kNormL2 = 2, kNormInf = 3 };
 enum { kFmtFused = 0, kFmtNibble = 1, kFmtByte = 2 };
 
 constexpr uint32_t kChunk = 2048;          // elements per workgroup in the chunked kernels (256 lanes x 8)
+constexpr uint32_t kNormChunk = 8192;      // elements per workgroup in the partial-norm pass (256 lanes x 8 quads)
 constexpr uint32_t kMaxOnePassBucket = 8192;  // largest bucket one workgroup keeps in registers
 
 struct DitherEncodeArgs {
@@ -43,7 +44,7 @@ struct DitherEncodeArgs {
     int pnorm; uint32_t s; int fmt;
     uint32_t k0, k1, worker; uint64_t index_offset;
     float* norms_out; uint8_t* code_out; uint8_t* sign_out;
-    double* first_partial;   // one per chunk      (two-pass path only)
+    double* first_partial;   // one per norm chunk (two-pass path only)
     double* head_partial;    // one per segment    (two-pass path only)
     float* inv_norm;         // one per segment    (two-pass path only)
 };

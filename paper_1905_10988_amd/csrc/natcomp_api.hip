@@ -111,7 +111,7 @@ size_t nc_dither_workspace_bytes(uint64_t d, uint32_t num_segments, uint32_t buc
     if (d == 0) return 0;
     if (!have_offsets && one_pass_bucket(nullptr, bucket)) return 0;
     const uint64_t nseg = nc_segment_count(d, num_segments, bucket, have_offsets);
-    const uint64_t chunks = (d + kChunk - 1) / kChunk;
+    const uint64_t chunks = (d + kNormChunk - 1) / kNormChunk;
     return (size_t)(8 * chunks + 8 * nseg + align8(4 * nseg));
 }
 
@@ -142,7 +142,7 @@ nc_status nc_dither_encode(const float* x, uint64_t d, const uint64_t* seg_offse
     const size_t need = nc_dither_workspace_bytes(d, num_segments, bucket, seg_offsets != nullptr);
     if (!workspace || workspace_bytes < need || !aligned(workspace, 8)) return NC_ERR_WORKSPACE;
     const uint64_t nseg = nc_segment_count(d, num_segments, bucket, seg_offsets != nullptr);
-    const uint64_t chunks = (d + kChunk - 1) / kChunk;
+    const uint64_t chunks = (d + kNormChunk - 1) / kNormChunk;
     a.first_partial = static_cast<double*>(workspace);
     a.head_partial = a.first_partial + chunks;
     a.inv_norm = reinterpret_cast<float*>(a.head_partial + nseg);
