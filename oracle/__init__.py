@@ -70,6 +70,12 @@ def lib():
         L.orc_aggregate_dither.argtypes = [_f32p, _u64, _u8p, _u64, _u8p, _u64, _u32, _u64, _u64p, _u32, _u32, _u32,
                                            _f64p, _f32p, _f64p]
         L.orc_aggregate_dither.restype = None
+        L.orc_sparse_index.argtypes = [_u64, _u64, _u32, _u64]
+        L.orc_sparse_index.restype = _u64
+        L.orc_sparse_nat_encode.argtypes = [_f32p, _u64, _u64, ctypes.c_float, _u64, _u32, _u32p, _u8p, _u8p]
+        L.orc_sparse_nat_encode.restype = None
+        L.orc_sparse_nat_aggregate.argtypes = [_u32p, _u64, _u8p, _u64, _u8p, _u64, _u32, _u64, _u64, _f32p, _f64p, _f64p]
+        L.orc_sparse_nat_aggregate.restype = None
         L.orc_threads.argtypes = []
         L.orc_threads.restype = ctypes.c_int
         _lib = L
@@ -255,3 +261,44 @@ def aggregate_dither(norms, code, sign, d, s, offsets=None, bucket=0):
                                sstride, n, d, _ptr(off, _u64p), nseg, bucket, s, _ptr(o64, _f64p), _ptr(o32, _f32p),
                                _ptr(oa, _f64p))
     return o64, o32, oa
+
+
+# ------------------------------------------------ random sparsification composed with C_nat
+DOMAIN_SPARSE = 2
+
+
+def sparse_index(d, seed, worker, j):
+    """pi(j): the j-th kept coordinate of the keyed permutation of [0, d)."""
+    assert 0 <= j < d <= 1 << 32
+    return int(lib().orc_sparse_index(d, seed, worker, j))
+
+
+def sparse_nat_encode(x, k, scale, seed, worker=0):
+    """(indices uint32[k], exponent plane uint8[k], sign plane uint8[ceil(k/8)])."""
+    x = _c(x, np.float32)
+    d = x.size
+    assert 0 < k <= d <= 1 << 32
+    idx = np.zeros(k, np.uint32)
+    exp = np.zeros(k, np.uint8)
+    sign = np.zeros((k + 7) // 8, np.uint8)
+    lib().orc_sparse_nat_encode(_ptr(x, _f32p), d, k, np.float32(scale), seed, worker, _ptr(idx, _u32p),
+                                _ptr(exp, _u8p), _ptr(sign, _u8p))
+    return idx, exp, sign
+
+
+def sparse_nat_aggregate(idx, exp, sign, k, d):
+    """idx (n, >=k) uint32, exp (n, >=k) uint8, sign (n, >=ceil(k/8)) uint8 -> (binary32 sum in worker
+    order, double sum, sum of magnitudes), dense vectors of length d."""
+    idx = _c(idx, np.uint32)
+    exp = _c(exp, np.uint8)
+    sign = _c(sign, np.uint8)
+    n = idx.shape[0]
+    assert idx.ndim == 2 and exp.shape[0] == n and sign.shape[0] == n
+    assert idx.shape[1] >= k and exp.shape[1] >= k and sign.shape[1] >= (k + 7) // 8
+    assert int(idx[:, :k].max()) < d
+    o32 = np.zeros(d, np.float32)
+    o64 = np.zeros(d, np.float64)
+    oa = np.zeros(d, np.float64)
+    lib().orc_sparse_nat_aggregate(_ptr(idx, _u32p), idx.shape[1], _ptr(exp, _u8p), exp.shape[1], _ptr(sign, _u8p),
+                                   sign.shape[1], n, k, d, _ptr(o32, _f32p), _ptr(o64, _f64p), _ptr(oa, _f64p))
+    return o32, o64, oa

@@ -24,6 +24,9 @@
  *   orc_dither_encode    y_i = |x_i| / ||x||_p, xi(y_i), sign(x_i); norm per caller segment.
  *   orc_dither_decode    ||x||_p * sign * level.
  *   orc_aggregate_*      Algorithm 1, the master's sum over workers of the decompressed updates.
+ *   orc_sparse_*         Appendix "Sparsification - formal definition": S^q(x) = (d/q) xi o x with
+ *                        exactly q kept coordinates, composed with C_nat (composition theorem);
+ *                        how the q coordinates are drawn (a keyed permutation) is this build's choice.
  *   orc_philox4x32_10    Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
  *                        as 1, 2, 3" (SC'11), Philox-4x32 with 10 rounds.  The paper only
  *                        asks for a Bernoulli draw per element; the generator, its keying by
@@ -435,3 +438,99 @@ int orc_threads(void) { return omp_get_max_threads(); }
 #else
 int orc_threads(void) { return 1; }
 #endif
+
+/* ------------------------------------------------------------------------ */
+/* Random sparsification composed with natural compression                  */
+/* ------------------------------------------------------------------------ */
+
+/* Random sparsification S^q (formal definition in the appendix on sparsification):
+ * S^q(x) = (d/q) xi o x with xi uniform over the binary vectors with exactly q
+ * ones; C_nat o S^q is then in B(9d/8q - 1) by the composition theorem.
+ *
+ * The paper does not say how xi is drawn.  Here the q kept coordinates are the
+ * images pi(0), ..., pi(q-1) of a keyed pseudo-random permutation pi of [0, d):
+ * a 4-round balanced Feistel network on 2h bits (2^(2h) >= d, h >= 1) whose
+ * round keys are the four words of one Philox call (counter (0, 0, worker, 2),
+ * key = seed), with cycle walking (apply the network again while the value is
+ * >= d), so pi is a bijection of [0, d) and any j can be evaluated on its own. */
+enum { ORC_DOMAIN_SPARSE = 2 };
+
+static uint32_t feistel_round_fn(uint32_t r, uint32_t key)
+{
+    uint32_t t = r * 0x9E3779B1u + key;
+    t ^= t >> 16; t *= 0x85EBCA6Bu;
+    t ^= t >> 13; t *= 0xC2B2AE35u;
+    t ^= t >> 16;
+    return t;
+}
+
+static uint32_t half_bits(uint64_t d)
+{
+    uint32_t h = 1;
+    while (h < 16 && ((uint64_t)1 << (2 * h)) < d) ++h;
+    return h;
+}
+
+/* pi(j) for 0 <= j < d <= 2^32. */
+uint64_t orc_sparse_index(uint64_t d, uint64_t seed, uint32_t worker, uint64_t j)
+{
+    uint32_t ctr[4] = { 0, 0, worker, ORC_DOMAIN_SPARSE };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t rk[4];
+    orc_philox4x32_10(ctr, key, rk);
+    uint32_t h = half_bits(d);
+    uint32_t mask = (h == 16) ? 0xFFFFu : ((1u << h) - 1u);
+    uint64_t v = j;
+    do {
+        uint32_t left = (uint32_t)(v >> h) & mask, right = (uint32_t)v & mask;
+        for (int round = 0; round < 4; ++round) {
+            uint32_t next = left ^ (feistel_round_fn(right, rk[round]) & mask);
+            left = right;
+            right = next;
+        }
+        v = ((uint64_t)left << h) | right;
+    } while (v >= d);
+    return v;
+}
+
+/* Worker's message: for j < k the kept index i = pi(j), and C_nat applied to
+ * fl(scale * x[i]) (scale = d/k makes the operator unbiased) with the random
+ * word of dense position i in the C_nat stream.  Exponent byte j and sign bit j
+ * of the planes belong to idx_out[j]. */
+void orc_sparse_nat_encode(const float *x, uint64_t d, uint64_t k, float scale, uint64_t seed,
+                           uint32_t worker, uint32_t *idx_out, uint8_t *exp_out, uint8_t *sign_out)
+{
+    memset(sign_out, 0, (k + 7) / 8);
+    for (uint64_t j = 0; j < k; ++j) {
+        uint64_t i = orc_sparse_index(d, seed, worker, j);
+        volatile float v = scale * x[i];
+        uint32_t u = f32_bits(v);
+        uint32_t r = orc_random_word(seed, worker, ORC_DOMAIN_NAT, i);
+        idx_out[j] = (uint32_t)i;
+        exp_out[j] = (uint8_t)orc_nat_round(u, r);
+        sign_out[j >> 3] |= (uint8_t)((u >> 31) << (j & 7));
+    }
+}
+
+/* Dense sum of n sparse messages: out starts at zero; workers are added in
+ * the order w = 0, 1, ...; out32 in binary32, out64 in double, abs64 = sum of
+ * magnitudes.  Strides are in elements of the respective arrays. */
+void orc_sparse_nat_aggregate(const uint32_t *idx, uint64_t idx_stride, const uint8_t *exp, uint64_t exp_stride,
+                              const uint8_t *sign, uint64_t sign_stride, uint32_t n, uint64_t k, uint64_t d,
+                              float *out32, double *out64, double *abs64)
+{
+    for (uint64_t i = 0; i < d; ++i) {
+        if (out32) out32[i] = 0.0f;
+        if (out64) out64[i] = 0.0;
+        if (abs64) abs64[i] = 0.0;
+    }
+    for (uint32_t w = 0; w < n; ++w) {
+        for (uint64_t j = 0; j < k; ++j) {
+            uint64_t i = idx[(uint64_t)w * idx_stride + j];
+            float v = nat_value(exp + (uint64_t)w * exp_stride, sign + (uint64_t)w * sign_stride, j);
+            if (out32) { volatile float t = out32[i] + v; out32[i] = t; }
+            if (out64) out64[i] += (double)v;
+            if (abs64) abs64[i] += fabs((double)v);
+        }
+    }
+}
