@@ -157,6 +157,40 @@ typedef struct {
 
 nc_status nc_aggregate_sum(const nc_agg_desc *desc, float *out, void *stream);
 
+/* ----------------------------------------------------------------------------------------
+ * Random sparsification composed with natural compression, C_nat o S^k (formal definition
+ * of S^q in the appendix on sparsification: S^q(x) = (d/q) xi o x with exactly q kept
+ * coordinates; C_nat o S^q is in B(9d/8q - 1) by the composition theorem of Sec. 2).
+ *
+ * The k kept coordinates of a worker are pi(0), ..., pi(k-1) for a keyed pseudo-random
+ * permutation pi of [0, d): a 4-round balanced Feistel network on 2h bits (2^(2h) >= d)
+ * with cycle walking, its round keys the four words of the Philox call with counter
+ * (0, 0, worker, 2) and key = seed; the round function is
+ * t = R*0x9E3779B1 + key; t ^= t>>16; t *= 0x85EBCA6B; t ^= t>>13; t *= 0xC2B2AE35; t ^= t>>16.
+ * Entry j of the message: idx_out[j] = i = pi(j); exponent byte j and sign bit j are
+ * C_nat(fl(scale * x[i])) with the random word of dense position i in the C_nat stream
+ * (so k = d, scale = 1 reproduces nc_nat_encode).  scale = d/k makes the operator unbiased.
+ *
+ *   x DEVICE d floats (1 <= d <= 2^32, 1 <= k <= d);  idx_out DEVICE k uint32;
+ *   exp_out DEVICE k bytes;  sign_out DEVICE ceil(k/8) bytes.
+ * The batch form encodes n workers in one launch (strides in elements of each array).
+ * -------------------------------------------------------------------------------------- */
+nc_status nc_sparse_nat_encode(const float *x, uint64_t d, uint64_t k, float scale, uint64_t seed,
+                               uint32_t worker, uint32_t *idx_out, uint8_t *exp_out, uint8_t *sign_out,
+                               void *stream);
+nc_status nc_sparse_nat_encode_batch(const float *x, size_t x_stride, uint32_t n, uint64_t d, uint64_t k,
+                                     float scale, uint64_t seed, uint32_t first_worker, uint32_t *idx_out,
+                                     size_t idx_stride, uint8_t *exp_out, size_t exp_stride, uint8_t *sign_out,
+                                     size_t sign_stride, void *stream);
+
+/* Master's sum of n sparse messages (Algorithm 1): out[0..d) is zero-filled, then worker
+ * w = 0, 1, ..., n-1 adds its k decoded values at its indices, in binary32 and in this
+ * order (one launch per worker, so the result is reproducible).  Indices >= d are ignored;
+ * a worker's indices must be distinct.  out DEVICE d floats. */
+nc_status nc_sparse_nat_aggregate(const uint32_t *idx, size_t idx_stride, const uint8_t *exp, size_t exp_stride,
+                                  const uint8_t *sign, size_t sign_stride, uint32_t n, uint64_t k, uint64_t d,
+                                  float *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -286,9 +286,9 @@ def sparse_nat_encode(x, k, scale, seed, worker=0):
     return idx, exp, sign
 
 
-def sparse_nat_aggregate(idx, exp, sign, k, d):
+def sparse_nat_aggregate(idx, exp, sign, k, d, only32=False):
     """idx (n, >=k) uint32, exp (n, >=k) uint8, sign (n, >=ceil(k/8)) uint8 -> (binary32 sum in worker
-    order, double sum, sum of magnitudes), dense vectors of length d."""
+    order, double sum, sum of magnitudes), dense vectors of length d (only32: the last two are None)."""
     idx = _c(idx, np.uint32)
     exp = _c(exp, np.uint8)
     sign = _c(sign, np.uint8)
@@ -297,8 +297,8 @@ def sparse_nat_aggregate(idx, exp, sign, k, d):
     assert idx.shape[1] >= k and exp.shape[1] >= k and sign.shape[1] >= (k + 7) // 8
     assert int(idx[:, :k].max()) < d
     o32 = np.zeros(d, np.float32)
-    o64 = np.zeros(d, np.float64)
-    oa = np.zeros(d, np.float64)
+    o64 = None if only32 else np.zeros(d, np.float64)
+    oa = None if only32 else np.zeros(d, np.float64)
     lib().orc_sparse_nat_aggregate(_ptr(idx, _u32p), idx.shape[1], _ptr(exp, _u8p), exp.shape[1], _ptr(sign, _u8p),
                                    sign.shape[1], n, k, d, _ptr(o32, _f32p), _ptr(o64, _f64p), _ptr(oa, _f64p))
     return o32, o64, oa

@@ -61,6 +61,25 @@ hipError_t launch_dither_segment_encode(const DitherEncodeArgs& a, bool fast, hi
 // Decode (n = 1) and fused decode-and-sum (n > 1) of dithering codes.
 hipError_t launch_dither_aggregate(const DitherAggregateArgs& a, bool fast, hipStream_t stream);
 
+struct SparseEncodeArgs {
+    const float* x; size_t x_stride;
+    uint64_t d, k; uint32_t h;                 // 2h = bits of the Feistel network, 2^(2h) >= d
+    float scale;
+    uint32_t k0, k1, first_worker;
+    uint32_t* idx_out; size_t idx_stride;      // elements between workers
+    uint8_t* exp_out; size_t exp_stride;
+    uint8_t* sign_out; size_t sign_stride;
+    bool vec;                                  // idx_out 16-byte and exp_out 8-byte aligned for every worker
+};
+struct SparseScatterArgs {
+    const uint32_t* idx; const uint8_t* exp; const uint8_t* sign; uint64_t k, d; float* out;
+};
+hipError_t launch_sparse_nat_encode(const SparseEncodeArgs& a, uint32_t n, hipStream_t stream);
+// Zero-fills out[0..d) and adds the n messages, one launch per worker in worker order.
+hipError_t launch_sparse_nat_aggregate(const uint32_t* idx, size_t idx_stride, const uint8_t* exp, size_t exp_stride,
+                                       const uint8_t* sign, size_t sign_stride, uint32_t n, uint64_t k, uint64_t d,
+                                       float* out, bool out_aligned, hipStream_t stream);
+
 // `fast` promises the alignment the vector path needs (checked by the caller).
 hipError_t launch_nat_encode(const NatEncodeArgs& a, uint32_t n, bool fast, hipStream_t stream);
 hipError_t launch_nat_decode(const NatDecodeArgs& a, bool fast, hipStream_t stream);

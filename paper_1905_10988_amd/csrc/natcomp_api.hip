@@ -178,6 +178,39 @@ nc_status nc_dither_decode(const float* norms, const uint8_t* code, const uint8_
     return dither_aggregate(norms, 0, code, 0, sign, 0, 1, d, seg_offsets, num_segments, bucket, s, out, stream);
 }
 
+nc_status nc_sparse_nat_encode_batch(const float* x, size_t x_stride, uint32_t n, uint64_t d, uint64_t k, float scale,
+                                     uint64_t seed, uint32_t first_worker, uint32_t* idx_out, size_t idx_stride,
+                                     uint8_t* exp_out, size_t exp_stride, uint8_t* sign_out, size_t sign_stride,
+                                     void* stream) {
+    if (n == 0 || n > 65535 || d == 0 || d > (1ull << 32) || k == 0 || k > d) return NC_ERR_INVALID;
+    if (!x || !idx_out || !exp_out || !sign_out) return NC_ERR_NULL;
+    if (n > 1 && (x_stride < d || idx_stride < k || exp_stride < k || sign_stride < (k + 7) / 8)) return NC_ERR_INVALID;
+    SparseEncodeArgs a{};
+    a.x = x; a.x_stride = x_stride; a.d = d; a.k = k; a.scale = scale;
+    a.h = 1;
+    while (a.h < 16 && (1ull << (2 * a.h)) < d) ++a.h;
+    a.k0 = (uint32_t)seed; a.k1 = (uint32_t)(seed >> 32); a.first_worker = first_worker;
+    a.idx_out = idx_out; a.idx_stride = idx_stride; a.exp_out = exp_out; a.exp_stride = exp_stride;
+    a.sign_out = sign_out; a.sign_stride = sign_stride;
+    a.vec = aligned(idx_out, 16) && aligned(exp_out, 8) && (n == 1 || ((idx_stride & 3) == 0 && (exp_stride & 7) == 0));
+    return from_hip(launch_sparse_nat_encode(a, n, (hipStream_t)stream));
+}
+
+nc_status nc_sparse_nat_encode(const float* x, uint64_t d, uint64_t k, float scale, uint64_t seed, uint32_t worker,
+                               uint32_t* idx_out, uint8_t* exp_out, uint8_t* sign_out, void* stream) {
+    return nc_sparse_nat_encode_batch(x, 0, 1, d, k, scale, seed, worker, idx_out, 0, exp_out, 0, sign_out, 0, stream);
+}
+
+nc_status nc_sparse_nat_aggregate(const uint32_t* idx, size_t idx_stride, const uint8_t* exp, size_t exp_stride,
+                                  const uint8_t* sign, size_t sign_stride, uint32_t n, uint64_t k, uint64_t d,
+                                  float* out, void* stream) {
+    if (n == 0 || d == 0 || d > (1ull << 32) || k == 0 || k > d) return NC_ERR_INVALID;
+    if (!idx || !exp || !sign || !out) return NC_ERR_NULL;
+    if (n > 1 && (idx_stride < k || exp_stride < k || sign_stride < (k + 7) / 8)) return NC_ERR_INVALID;
+    return from_hip(launch_sparse_nat_aggregate(idx, idx_stride, exp, exp_stride, sign, sign_stride, n, k, d, out,
+                                                aligned(out, 16), (hipStream_t)stream));
+}
+
 nc_status nc_aggregate_sum(const nc_agg_desc* desc, float* out, void* stream) {
     if (!desc) return NC_ERR_NULL;
     if (desc->n == 0 || desc->d > kMaxD) return NC_ERR_INVALID;

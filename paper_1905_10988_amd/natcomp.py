@@ -65,6 +65,12 @@ def lib():
                                        _vp, _vp, _vp, _vp, _sz, _vp]
         L.nc_dither_decode.argtypes = [_vp, _vp, _vp, _u64, _vp, _u32, _u32, _u32, _vp, _vp]
         L.nc_aggregate_sum.argtypes = [ctypes.POINTER(AggDesc), _vp, _vp]
+        L.nc_sparse_nat_encode.argtypes = [_vp, _u64, _u64, ctypes.c_float, _u64, _u32, _vp, _vp, _vp, _vp]
+        L.nc_sparse_nat_encode_batch.argtypes = [_vp, _sz, _u32, _u64, _u64, ctypes.c_float, _u64, _u32, _vp, _sz,
+                                                 _vp, _sz, _vp, _sz, _vp]
+        L.nc_sparse_nat_aggregate.argtypes = [_vp, _sz, _vp, _sz, _vp, _sz, _u32, _u64, _u64, _vp, _vp]
+        for name in ("nc_sparse_nat_encode", "nc_sparse_nat_encode_batch", "nc_sparse_nat_aggregate"):
+            getattr(L, name).restype = ctypes.c_int
         for name in ("nc_nat_encode", "nc_nat_encode_batch", "nc_nat_decode", "nc_dither_encode",
                      "nc_dither_decode", "nc_aggregate_sum"):
             getattr(L, name).restype = ctypes.c_int
@@ -248,6 +254,58 @@ def aggregate_sum(kind, d, code, sign=None, norms=None, s=0, seg_offsets=None, b
     _dev(out, torch.float32, "out")
     assert out.numel() >= d
     _check(lib().nc_aggregate_sum(ctypes.byref(desc), _ptr(out), _stream()))
+    return out
+
+
+# ------------------------------------------------------------------ sparsification + C_nat
+def sparse_nat_encode_batch(x, k, scale, seed, first_worker=0, d=None, idx_out=None, exp_out=None, sign_out=None):
+    """nc_sparse_nat_encode_batch: x is (n, row) float32; returns (idx int32-typed uint32 values (n, ks),
+    exp (n, es), sign (n, ss)) with strides rounded up so every row is 256-byte aligned."""
+    x = _dev(x, torch.float32, "x")
+    assert x.dim() == 2
+    n, row = x.shape
+    d = row if d is None else d
+    if idx_out is None:
+        idx_out = torch.empty((n, plane_stride(4 * k) // 4), dtype=torch.int32, device=x.device)
+    if exp_out is None:
+        exp_out = torch.empty((n, plane_stride(k)), dtype=torch.uint8, device=x.device)
+    if sign_out is None:
+        sign_out = torch.empty((n, plane_stride(sign_bytes(k))), dtype=torch.uint8, device=x.device)
+    _dev(idx_out, torch.int32, "idx_out")
+    _dev(exp_out, torch.uint8, "exp_out")
+    _dev(sign_out, torch.uint8, "sign_out")
+    assert idx_out.shape[0] == n and idx_out.shape[1] >= k and exp_out.shape[1] >= k
+    _check(lib().nc_sparse_nat_encode_batch(_ptr(x), row, n, d, k, float(scale), seed, first_worker, _ptr(idx_out),
+                                            idx_out.shape[1], _ptr(exp_out), exp_out.shape[1], _ptr(sign_out),
+                                            sign_out.shape[1], _stream()))
+    return idx_out, exp_out, sign_out
+
+
+def sparse_nat_encode(x, k, scale, seed, worker=0):
+    """nc_sparse_nat_encode on a 1-D tensor: (idx (k,), exp (k,), sign (ceil(k/8),))."""
+    x = _dev(x, torch.float32, "x")
+    d = x.numel()
+    idx = torch.empty(k, dtype=torch.int32, device=x.device)
+    exp = torch.empty(k, dtype=torch.uint8, device=x.device)
+    sign = torch.empty(sign_bytes(k), dtype=torch.uint8, device=x.device)
+    _check(lib().nc_sparse_nat_encode(_ptr(x), d, k, float(scale), seed, worker, _ptr(idx), _ptr(exp), _ptr(sign),
+                                      _stream()))
+    return idx, exp, sign
+
+
+def sparse_nat_aggregate(idx, exp, sign, k, d, out=None):
+    """nc_sparse_nat_aggregate over the rows of 2-D tensors (row w = worker w)."""
+    idx = _dev(idx, torch.int32, "idx")
+    exp = _dev(exp, torch.uint8, "exp")
+    sign = _dev(sign, torch.uint8, "sign")
+    assert idx.dim() == 2 and exp.dim() == 2 and sign.dim() == 2
+    n = idx.shape[0]
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=idx.device)
+    _dev(out, torch.float32, "out")
+    assert out.numel() >= d
+    _check(lib().nc_sparse_nat_aggregate(_ptr(idx), idx.shape[1], _ptr(exp), exp.shape[1], _ptr(sign), sign.shape[1],
+                                         n, k, d, _ptr(out), _stream()))
     return out
 
 

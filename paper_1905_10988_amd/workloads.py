@@ -109,6 +109,17 @@ def bucketed_gaussian(worker, d=D_VGG16, bucket=BUCKET, scale_lo=1e-6, scale_hi=
     return x
 
 
+D_BERT_LARGE = 335_000_000     # config 5 (a BERT-large-sized parameter count)
+
+
+def dense_gaussian(worker, d=D_BERT_LARGE, sigma=1e-2, seed=1005):
+    """Config 5: entries i.i.d. N(0, 1e-4) (sigma = 1e-2)."""
+    rng = _rng([seed, 1 + worker])
+    x = rng.standard_normal(d, dtype=np.float32)
+    x *= np.float32(sigma)
+    return x
+
+
 def edge_values():
     """A short vector of binary32 corner cases: signed zeros, subnormals, exact powers of
     two, values next to powers of two, the largest finite value, infinities and a NaN."""
@@ -154,4 +165,13 @@ def bucketed_gaussian_device(worker, d=D_VGG16, bucket=BUCKET, scale_lo=1e-6, sc
     x = torch.empty(d, dtype=torch.float32, device=device) if out is None else out
     x.normal_(generator=g)
     x *= torch.repeat_interleave(torch.from_numpy(scale).to(device), bucket)[:d]
+    return x
+
+
+def dense_gaussian_device(worker, d=D_BERT_LARGE, sigma=1e-2, seed=1005, device="cuda", out=None):
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed * 1000 + worker)
+    x = torch.empty(d, dtype=torch.float32, device=device) if out is None else out
+    x.normal_(0.0, sigma, generator=g)
     return x

@@ -1,0 +1,122 @@
+"""GPU parity of C_nat o S^k and its dense scatter-sum: indices, exponent and sign planes
+bit-exact with the oracle; the dense binary32 sum bit-exact with the oracle's worker-ordered
+binary32 sum and within 1e-5 * sum|v| of its double sum."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import Guarded, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def nc():
+    from paper_1905_10988_amd import natcomp
+    natcomp.lib()
+    assert torch.cuda.is_available()
+    return natcomp
+
+
+@pytest.fixture(scope="module")
+def wl():
+    from paper_1905_10988_amd import workloads
+    return workloads
+
+
+def check_message(nc, oracle, x, k, scale, seed, worker):
+    idx, exp, sign = nc.sparse_nat_encode(dev(x), k, scale, seed, worker)
+    torch.cuda.synchronize()
+    io, eo, so = oracle.sparse_nat_encode(x, k, scale, seed, worker)
+    assert np.array_equal(host(idx).view(np.uint32), io)
+    assert np.array_equal(host(exp), eo)
+    assert np.array_equal(host(sign), so)
+    return idx, exp, sign
+
+
+@pytest.mark.parametrize("d,k", [(1, 1), (2, 1), (7, 7), (8, 8), (9, 5), (1000, 10), (1000, 1000), (4099, 333),
+                                 (65536, 655), (65537, 8193), (1_000_003, 10_001)])
+def test_messages_match_oracle(nc, oracle, wl, d, k):
+    x = wl.dense_gaussian(0, d=d, seed=d + k)
+    for seed, worker in ((0, 0), (12345678901234, 5)):
+        check_message(nc, oracle, x, k, np.float32(d / k), seed, worker)
+
+
+def test_k_equal_d_reproduces_dense_codes(nc, oracle, wl):
+    """S^d is the identity: with k = d and scale 1 the sparse message is the dense C_nat code in
+    permuted order (same random word per dense position)."""
+    d = 20011
+    x = wl.config1(d=d, seed=6)
+    idx, exp, sign = check_message(nc, oracle, x, d, 1.0, 9, 2)
+    e_dense, s_dense = nc.nat_encode(dev(x), 9, worker=2)
+    i = host(idx).astype(np.int64)
+    assert sorted(i.tolist()) == list(range(d))
+    assert np.array_equal(host(exp), host(e_dense)[i])
+    sd = np.unpackbits(host(s_dense), bitorder="little")[:d]
+    assert np.array_equal(np.unpackbits(host(sign), bitorder="little")[:d], sd[i])
+
+
+@pytest.mark.parametrize("n", [1, 2, 8, 11])
+def test_batch_and_aggregate(nc, oracle, wl, n):
+    d, k = 50_003, 5_001
+    rows = np.stack([wl.dense_gaussian(w, d=d, seed=77) for w in range(n)])
+    scale = np.float32(d / k)
+    idx, exp, sign = nc.sparse_nat_encode_batch(dev(rows), k, scale, seed=3)
+    out = Guarded(d, torch.float32)
+    nc.sparse_nat_aggregate(idx, exp, sign, k, d, out=out.t)
+    torch.cuda.synchronize()
+    got = out.check()
+    ih, eh, sh = host(idx).view(np.uint32), host(exp), host(sign)
+    for w in range(n):
+        io, eo, so = oracle.sparse_nat_encode(rows[w], k, scale, 3, w)
+        assert np.array_equal(ih[w, :k], io) and np.array_equal(eh[w, :k], eo)
+        assert np.array_equal(sh[w, : so.size], so)
+    o32, o64, oa = oracle.sparse_nat_aggregate(ih, eh, sh, k, d)
+    assert np.array_equal(got.view(np.uint32), o32.view(np.uint32))
+    assert np.all(np.abs(got.astype(np.float64) - o64) <= 1e-5 * oa)
+
+
+def test_unaligned_output_and_tiny_sizes(nc, oracle, wl):
+    d, k, n = 1001, 77, 3
+    rows = np.stack([wl.dense_gaussian(w, d=d, seed=5) for w in range(n)])
+    idx, exp, sign = nc.sparse_nat_encode_batch(dev(rows), k, 13.0, seed=8)
+    buf = torch.full((d + 3,), 7.0, dtype=torch.float32, device="cuda")
+    nc.sparse_nat_aggregate(idx, exp, sign, k, d, out=buf[1: d + 1])
+    got = host(buf)
+    assert got[0] == 7.0 and got[d + 1] == 7.0 and got[d + 2] == 7.0
+    o32, _, _ = oracle.sparse_nat_aggregate(host(idx).view(np.uint32), host(exp), host(sign), k, d)
+    assert np.array_equal(got[1: d + 1].view(np.uint32), o32.view(np.uint32))
+
+
+def test_argument_errors(nc):
+    x = torch.zeros(100, dtype=torch.float32, device="cuda")
+    with pytest.raises(nc.NatcompError, match="INVALID"):
+        nc.sparse_nat_encode(x, 101, 1.0, 0)
+
+
+def test_config5_full_size_two_workers(nc, oracle, wl):
+    """Config 5 at its full d = 335,000,000 and k = d/100, two of the eight workers: messages in
+    full against the oracle, and the whole dense sum against the oracle's."""
+    d = wl.D_BERT_LARGE
+    k = d // 100
+    n = 2
+    scale = np.float32(d / k)
+    xdev = torch.empty((n, d), dtype=torch.float32, device="cuda")
+    xs = []
+    for w in range(n):
+        x = wl.dense_gaussian(w)
+        xs.append(x)
+        xdev[w] = torch.from_numpy(x).cuda()
+    idx, exp, sign = nc.sparse_nat_encode_batch(xdev, k, scale, seed=0)
+    out = nc.sparse_nat_aggregate(idx, exp, sign, k, d)
+    torch.cuda.synchronize()
+    ih, eh, sh = host(idx).view(np.uint32), host(exp), host(sign)
+    for w in range(n):
+        io, eo, so = oracle.sparse_nat_encode(xs[w], k, scale, 0, w)
+        assert np.array_equal(ih[w, :k], io) and np.array_equal(eh[w, :k], eo)
+        assert np.array_equal(sh[w, : so.size], so)
+    del xs
+    o32, _, _ = oracle.sparse_nat_aggregate(ih, eh, sh, k, d, only32=True)
+    got = host(out)
+    assert np.array_equal(got.view(np.uint32), o32.view(np.uint32))
+    assert np.count_nonzero(got) > 2 * k * 0.98
