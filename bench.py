@@ -105,6 +105,27 @@ def secondary_kernels(nc, wl, torch, np):
                                                       out=out4), reps=10)
     res["config4_dither_inf_4_aggregate_n8"] = _entry(ms, 8.0 * d4 + 4.0 * nb * n, 4.0 * d4 * n,
                                                      "8 x 0.5 B read + 4 B written per output element, plus norms")
+    del xs, norms4, code4, out4
+    # config 5: C_nat o S^k, d = 335,000,000, k = d/100, 8 workers, dense scatter-sum
+    d5, k5 = wl.D_BERT_LARGE, wl.D_BERT_LARGE // 100
+    x5 = torch.empty((n, d5), dtype=torch.float32, device="cuda")
+    for w in range(n):
+        wl.dense_gaussian_device(w, out=x5[w])
+    idx = torch.empty((n, nc.plane_stride(4 * k5) // 4), dtype=torch.int32, device="cuda")
+    exp5 = torch.empty((n, nc.plane_stride(k5)), dtype=torch.uint8, device="cuda")
+    sign5 = torch.empty((n, nc.plane_stride(nc.sign_bytes(k5))), dtype=torch.uint8, device="cuda")
+    out5 = torch.empty(d5, dtype=torch.float32, device="cuda")
+    scale = float(np.float32(d5 / k5))
+    ms = _time_ms(torch, np, lambda: nc.sparse_nat_encode_batch(x5, k5, scale, 0, idx_out=idx, exp_out=exp5,
+                                                                sign_out=sign5), reps=10)
+    res["config5_sparse_nat_encode_x8"] = _entry(
+        ms, n * k5 * (4 + 4 + 1.125), 4.0 * d5 * n,
+        "8 workers in one launch; per kept entry a 4 B gather, 4 B index + 1.125 B code written "
+        "(the gather really moves a 32-64 B sector per entry)")
+    ms = _time_ms(torch, np, lambda: nc.sparse_nat_aggregate(idx, exp5, sign5, k5, d5, out=out5), reps=10)
+    res["config5_sparse_nat_aggregate_n8"] = _entry(
+        ms, 4.0 * d5 + n * k5 * (4 + 1.125 + 8), 4.0 * d5 * n,
+        "zero-fill of the dense vector (4 B per coordinate) + 8 launches of k random 4 B read-modify-writes")
     return res
 
 

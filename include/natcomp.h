@@ -163,10 +163,12 @@ nc_status nc_aggregate_sum(const nc_agg_desc *desc, float *out, void *stream);
  * coordinates; C_nat o S^q is in B(9d/8q - 1) by the composition theorem of Sec. 2).
  *
  * The k kept coordinates of a worker are pi(0), ..., pi(k-1) for a keyed pseudo-random
- * permutation pi of [0, d): a 4-round balanced Feistel network on 2h bits (2^(2h) >= d)
- * with cycle walking, its round keys the four words of the Philox call with counter
- * (0, 0, worker, 2) and key = seed; the round function is
- * t = R*0x9E3779B1 + key; t ^= t>>16; t *= 0x85EBCA6B; t ^= t>>13; t *= 0xC2B2AE35; t ^= t>>16.
+ * permutation pi of [0, d): a 4-round alternating Feistel network on b = ceil(log2 d) >= 2
+ * bits (high part A of floor(b/2) bits, low part B: A ^= F(B,k0), B ^= F(A,k1), A ^= F(B,k2),
+ * B ^= F(A,k3), each truncated to its part) with cycle walking; the round keys are the four
+ * words of the Philox call with counter (0, 0, worker, 2) and key = seed, and
+ * F(R, key): t = R*0x9E3779B1 + key; t ^= t>>16; t *= 0x85EBCA6B; t ^= t>>13; t *= 0xC2B2AE35;
+ * t ^= t>>16.
  * Entry j of the message: idx_out[j] = i = pi(j); exponent byte j and sign bit j are
  * C_nat(fl(scale * x[i])) with the random word of dense position i in the C_nat stream
  * (so k = d, scale = 1 reproduces nc_nat_encode).  scale = d/k makes the operator unbiased.

@@ -449,10 +449,11 @@ int orc_threads(void) { return 1; }
  *
  * The paper does not say how xi is drawn.  Here the q kept coordinates are the
  * images pi(0), ..., pi(q-1) of a keyed pseudo-random permutation pi of [0, d):
- * a 4-round balanced Feistel network on 2h bits (2^(2h) >= d, h >= 1) whose
- * round keys are the four words of one Philox call (counter (0, 0, worker, 2),
- * key = seed), with cycle walking (apply the network again while the value is
- * >= d), so pi is a bijection of [0, d) and any j can be evaluated on its own. */
+ * a 4-round alternating Feistel network on b = ceil(log2 d) bits (at least 2)
+ * whose round keys are the four words of one Philox call (counter
+ * (0, 0, worker, 2), key = seed), with cycle walking (apply the network again
+ * while the value is >= d; fewer than two applications on average), so pi is a
+ * bijection of [0, d) and any j can be evaluated on its own. */
 enum { ORC_DOMAIN_SPARSE = 2 };
 
 static uint32_t feistel_round_fn(uint32_t r, uint32_t key)
@@ -464,31 +465,36 @@ static uint32_t feistel_round_fn(uint32_t r, uint32_t key)
     return t;
 }
 
-static uint32_t half_bits(uint64_t d)
+/* Number of bits of the network: the smallest b >= 2 with 2^b >= d. */
+static uint32_t network_bits(uint64_t d)
 {
-    uint32_t h = 1;
-    while (h < 16 && ((uint64_t)1 << (2 * h)) < d) ++h;
-    return h;
+    uint32_t b = 2;
+    while (b < 32 && ((uint64_t)1 << b) < d) ++b;
+    return b;
 }
 
-/* pi(j) for 0 <= j < d <= 2^32. */
+/* pi(j) for 0 <= j < d <= 2^32.  The b-bit value is split into a high part A of
+ * floor(b/2) bits and a low part B of the remaining bits; the four rounds are
+ * A ^= F(B, k0), B ^= F(A, k1), A ^= F(B, k2), B ^= F(A, k3), each truncated to
+ * the width of the part it changes (every round is its own inverse, so the
+ * network is a bijection of [0, 2^b)). */
 uint64_t orc_sparse_index(uint64_t d, uint64_t seed, uint32_t worker, uint64_t j)
 {
     uint32_t ctr[4] = { 0, 0, worker, ORC_DOMAIN_SPARSE };
     uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
     uint32_t rk[4];
     orc_philox4x32_10(ctr, key, rk);
-    uint32_t h = half_bits(d);
-    uint32_t mask = (h == 16) ? 0xFFFFu : ((1u << h) - 1u);
+    uint32_t b = network_bits(d);
+    uint32_t bits_a = b / 2, bits_b = b - bits_a;
+    uint32_t mask_a = (1u << bits_a) - 1u, mask_b = (1u << bits_b) - 1u;
     uint64_t v = j;
     do {
-        uint32_t left = (uint32_t)(v >> h) & mask, right = (uint32_t)v & mask;
-        for (int round = 0; round < 4; ++round) {
-            uint32_t next = left ^ (feistel_round_fn(right, rk[round]) & mask);
-            left = right;
-            right = next;
-        }
-        v = ((uint64_t)left << h) | right;
+        uint32_t A = (uint32_t)(v >> bits_b) & mask_a, B = (uint32_t)v & mask_b;
+        A ^= feistel_round_fn(B, rk[0]) & mask_a;
+        B ^= feistel_round_fn(A, rk[1]) & mask_b;
+        A ^= feistel_round_fn(B, rk[2]) & mask_a;
+        B ^= feistel_round_fn(A, rk[3]) & mask_b;
+        v = ((uint64_t)A << bits_b) | B;
     } while (v >= d);
     return v;
 }

@@ -63,7 +63,7 @@ hipError_t launch_dither_aggregate(const DitherAggregateArgs& a, bool fast, hipS
 
 struct SparseEncodeArgs {
     const float* x; size_t x_stride;
-    uint64_t d, k; uint32_t h;                 // 2h = bits of the Feistel network, 2^(2h) >= d
+    uint64_t d, k; uint32_t bits;              // bits of the Feistel network: smallest b >= 2 with 2^b >= d
     float scale;
     uint32_t k0, k1, first_worker;
     uint32_t* idx_out; size_t idx_stride;      // elements between workers

@@ -187,8 +187,8 @@ nc_status nc_sparse_nat_encode_batch(const float* x, size_t x_stride, uint32_t n
     if (n > 1 && (x_stride < d || idx_stride < k || exp_stride < k || sign_stride < (k + 7) / 8)) return NC_ERR_INVALID;
     SparseEncodeArgs a{};
     a.x = x; a.x_stride = x_stride; a.d = d; a.k = k; a.scale = scale;
-    a.h = 1;
-    while (a.h < 16 && (1ull << (2 * a.h)) < d) ++a.h;
+    a.bits = 2;
+    while (a.bits < 32 && (1ull << a.bits) < d) ++a.bits;
     a.k0 = (uint32_t)seed; a.k1 = (uint32_t)(seed >> 32); a.first_worker = first_worker;
     a.idx_out = idx_out; a.idx_stride = idx_stride; a.exp_out = exp_out; a.exp_stride = exp_stride;
     a.sign_out = sign_out; a.sign_stride = sign_stride;

@@ -3,7 +3,7 @@
 // scatter-sum of n sparse messages (Algorithm 1's master sum).
 //
 // The k kept coordinates of a worker are pi(0..k-1) for a keyed permutation pi of [0, d):
-// a 4-round balanced Feistel network on 2h bits with cycle walking, round keys = the four
+// a 4-round alternating Feistel network on ceil(log2 d) bits with cycle walking, round keys = the four
 // words of one Philox call (counter (0, 0, worker, 2)).  Every j is independent, so the
 // selection is a plain parallel map.  One lane owns 8 consecutive j: it writes 8 indices,
 // 8 exponent bytes and one whole sign byte.
@@ -22,21 +22,16 @@ __device__ __forceinline__ uint32_t feistel_round_fn(uint32_t r, uint32_t key) {
     return t;
 }
 
-// pi(j): apply the network until the value falls below d (d <= 2^(2h)).
-__device__ __forceinline__ uint32_t sparse_index(uint64_t j, uint64_t d, uint32_t h, const uint32_t rk[4]) {
-    const uint32_t mask = (h == 16) ? 0xFFFFu : ((1u << h) - 1u);
-    uint64_t v = j;
-    do {
-        uint32_t left = (uint32_t)(v >> h) & mask, right = (uint32_t)v & mask;
-#pragma unroll
-        for (int round = 0; round < 4; ++round) {
-            const uint32_t next = left ^ (feistel_round_fn(right, rk[round]) & mask);
-            left = right;
-            right = next;
-        }
-        v = ((uint64_t)left << h) | right;
-    } while (v >= d);
-    return (uint32_t)v;
+// One application of the network to a b-bit value: high part A (floor(b/2) bits), low part B;
+// A ^= F(B,k0), B ^= F(A,k1), A ^= F(B,k2), B ^= F(A,k3), each truncated to its part's width.
+__device__ __forceinline__ uint32_t feistel_apply(uint32_t v, uint32_t bits_b, uint32_t mask_a, uint32_t mask_b,
+                                                  const uint32_t rk[4]) {
+    uint32_t A = (v >> bits_b) & mask_a, B = v & mask_b;
+    A ^= feistel_round_fn(B, rk[0]) & mask_a;
+    B ^= feistel_round_fn(A, rk[1]) & mask_b;
+    A ^= feistel_round_fn(B, rk[2]) & mask_a;
+    B ^= feistel_round_fn(A, rk[3]) & mask_b;
+    return (A << bits_b) | B;   // b <= 32 and A < 2^(b - bits_b): no overflow
 }
 
 // New exponent byte (top byte of the result) of u for the complemented random word rc:
@@ -55,10 +50,29 @@ __global__ __launch_bounds__(kBlock) void sparse_nat_encode_kernel(SparseEncodeA
     const uint32_t count = a.k - j0 < 8 ? (uint32_t)(a.k - j0) : 8u;
     uint32_t rk[4];
     philox4x32_10<false>(0u, 0u, worker, kDomainSparse, a.k0, a.k1, rk);
+    // Cycle walking (apply the network until the value is below d) takes a different number of
+    // rounds for every j.  The lane walks its 8 values as one queue, so a wavefront waits for the
+    // slowest lane's total, not for the slowest single walk 8 times over; finished indices go
+    // through an LDS column because a register array cannot be indexed by the queue position.
+    __shared__ uint32_t walked[8][kBlock];
+    {
+        const uint32_t bits_b = a.bits - a.bits / 2;
+        const uint32_t mask_a = (1u << (a.bits / 2)) - 1u, mask_b = (uint32_t)((1ull << bits_b) - 1ull);
+        uint32_t t = 0;
+        uint32_t v = (uint32_t)j0;           // d <= 2^32 and j < d: every value fits 32 bits
+        while (t < count) {
+            v = feistel_apply(v, bits_b, mask_a, mask_b, rk);
+            if ((uint64_t)v < a.d) {
+                walked[t][threadIdx.x] = v;
+                ++t;
+                v = (uint32_t)(j0 + t);
+            }
+        }
+    }
     uint32_t idx[8];
     float xv[8];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) idx[t] = (uint32_t)t < count ? sparse_index(j0 + t, a.d, a.h, rk) : 0u;
+    for (int t = 0; t < 8; ++t) idx[t] = (uint32_t)t < count ? walked[t][threadIdx.x] : 0u;
 #pragma unroll
     for (int t = 0; t < 8; ++t) xv[t] = x[idx[t]];  // idx 0 for the padding lanes: always in range
     uint32_t top[8], sb = 0;
