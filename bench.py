@@ -71,6 +71,17 @@ def secondary_kernels(nc, wl, torch, np):
     e, sg = nc.nat_encode(x, 0)
     ms = _time_ms(torch, np, lambda: nc.nat_decode(e, sg, d, out=out))
     res["nat_decode_d25.6M"] = _entry(ms, (1.125 + 4) * d, 4.0 * d, "1.125 B read + 4 B written per element")
+    # Algorithm 1's master step with C_M = C_nat at the config-2 shape: sum of 8 streams, re-compressed
+    xb = torch.empty((wl.NUM_WORKERS, (d + 63) // 64 * 64), dtype=torch.float32, device="cuda")
+    for w in range(wl.NUM_WORKERS):
+        xb[w, :d] = wl.layered_laplace_device(w, off)
+    eb, sb = nc.nat_encode_batch(xb, seed=0, d=d)
+    em = torch.empty(nc.nat_exp_bytes(d), dtype=torch.uint8, device="cuda")
+    sm = torch.empty(nc.sign_bytes(d), dtype=torch.uint8, device="cuda")
+    ms = _time_ms(torch, np, lambda: nc.master_nat(d, eb, sb, seed=1, exp_out=em, sign_out=sm))
+    res["master_nat_n8_d25.6M"] = _entry(ms, (wl.NUM_WORKERS * 1.125 + 1.125) * d, 4.0 * d * wl.NUM_WORKERS,
+                                         "fused decode+sum of 8 streams and C_nat of the sum: 9 B read + 1.125 B written per element")
+    del xb, eb, sb
     # config 3: D_nat^{2,8}, norm per layer tensor, encode then decode
     norms = torch.empty(nseg, dtype=torch.float32, device="cuda")
     code = torch.empty(nc.dither_code_bytes(d, 8), dtype=torch.uint8, device="cuda")

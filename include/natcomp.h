@@ -15,7 +15,8 @@
  *   - Randomness: element i of a call uses the 32-bit word of global index
  *     g = index_offset + i of the stream (seed, worker, operator): output word (g mod 4)
  *     of Philox-4x32-10 with key = (lo32(seed), hi32(seed)) and counter =
- *     (lo32(g/4), hi32(g/4), worker, domain), domain 0 for C_nat and 1 for D_nat.
+ *     (lo32(g/4), hi32(g/4), worker, domain), domain 0 for C_nat, 1 for D_nat, 2 for the
+ *     sparsifier's index selection and 3 for the master's C_nat.
  *     Results therefore do not depend on how a vector is split into calls or launches.
  *
  * Plane layouts (little-endian bit order inside a byte):
@@ -156,6 +157,17 @@ typedef struct {
 } nc_agg_desc;
 
 nc_status nc_aggregate_sum(const nc_agg_desc *desc, float *out, void *stream);
+
+/* Master step of Algorithm 1 with compression on the master too (bidirectional compression,
+ * Sec. 4): g = C_M(sum over workers of the decompressed updates) with C_M = C_nat.  One fused
+ * kernel sums the n C_nat streams as nc_aggregate_sum does (binary32, worker order) and
+ * naturally compresses the sum; the fp32 sum is never written.  The master's random words come
+ * from a stream of their own: domain 3, with `master` in the counter field the workers use for
+ * their id, element i at global index index_offset + i.
+ *   desc     HOST, kind = NC_KIND_NAT.
+ *   exp_out  DEVICE, nc_nat_exp_bytes(d) bytes;  sign_out  DEVICE, nc_sign_bytes(d) bytes. */
+nc_status nc_master_nat(const nc_agg_desc *desc, uint64_t seed, uint32_t master, uint64_t index_offset,
+                        uint8_t *exp_out, uint8_t *sign_out, void *stream);
 
 /* ----------------------------------------------------------------------------------------
  * Random sparsification composed with natural compression, C_nat o S^k (formal definition

@@ -76,6 +76,8 @@ def lib():
         L.orc_sparse_nat_encode.restype = None
         L.orc_sparse_nat_aggregate.argtypes = [_u32p, _u64, _u8p, _u64, _u8p, _u64, _u32, _u64, _u64, _f32p, _f64p, _f64p]
         L.orc_sparse_nat_aggregate.restype = None
+        L.orc_master_nat.argtypes = [_u8p, _u64, _u8p, _u64, _u32, _u64, _u64, _u32, _u64, _f32p, _u8p, _u8p]
+        L.orc_master_nat.restype = None
         L.orc_threads.argtypes = []
         L.orc_threads.restype = ctypes.c_int
         _lib = L
@@ -302,3 +304,23 @@ def sparse_nat_aggregate(idx, exp, sign, k, d, only32=False):
     lib().orc_sparse_nat_aggregate(_ptr(idx, _u32p), idx.shape[1], _ptr(exp, _u8p), exp.shape[1], _ptr(sign, _u8p),
                                    sign.shape[1], n, k, d, _ptr(o32, _f32p), _ptr(o64, _f64p), _ptr(oa, _f64p))
     return o32, o64, oa
+
+
+# ------------------------------------------------------------------ master-side compression
+DOMAIN_MASTER = 3
+
+
+def master_nat(exp, sign, d, seed, master=0, index_offset=0):
+    """Sum of the n decoded C_nat streams (binary32, worker order), then C_nat of the sum with the
+    master's stream: returns (sum, exponent plane, sign plane)."""
+    exp = _c(exp, np.uint8)
+    sign = _c(sign, np.uint8)
+    n = exp.shape[0]
+    assert exp.ndim == 2 and sign.ndim == 2 and sign.shape[0] == n
+    assert exp.shape[1] >= d and sign.shape[1] >= (d + 7) // 8
+    total = np.zeros(d, np.float32)
+    e = np.zeros(d, np.uint8)
+    s = np.zeros((d + 7) // 8, np.uint8)
+    lib().orc_master_nat(_ptr(exp, _u8p), exp.shape[1], _ptr(sign, _u8p), sign.shape[1], n, d, seed, master,
+                         index_offset, _ptr(total, _f32p), _ptr(e, _u8p), _ptr(s, _u8p))
+    return total, e, s

@@ -72,7 +72,7 @@ void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t ou
 }
 
 /* Domains keep the streams of different operators apart. */
-enum { ORC_DOMAIN_NAT = 0, ORC_DOMAIN_DITHER = 1 };
+enum { ORC_DOMAIN_NAT = 0, ORC_DOMAIN_DITHER = 1, ORC_DOMAIN_MASTER = 3 };
 
 /* The 32-bit uniform word of global element g: the counter is (g/4, worker,
  * domain), the key is the seed, and the element takes output word g mod 4.
@@ -124,8 +124,8 @@ uint64_t orc_nat_count_up(uint32_t u)
  * sign plane: bit (i mod 8) of sign_out[i/8] = sign bit of x[i]; the unused
  * high bits of the last sign byte are zero.  Element i draws the word of
  * global index index_offset + i. */
-void orc_nat_encode(const float *x, uint64_t d, uint64_t seed, uint32_t worker,
-                    uint64_t index_offset, uint8_t *exp_out, uint8_t *sign_out)
+static void nat_encode_domain(const float *x, uint64_t d, uint64_t seed, uint32_t worker, uint32_t domain,
+                              uint64_t index_offset, uint8_t *exp_out, uint8_t *sign_out)
 {
     uint64_t nsign = (d + 7) / 8;
     memset(sign_out, 0, nsign);
@@ -136,12 +136,18 @@ void orc_nat_encode(const float *x, uint64_t d, uint64_t seed, uint32_t worker,
             uint64_t i = (uint64_t)byte * 8 + bit;
             if (i >= d) break;
             uint32_t u = f32_bits(x[i]);
-            uint32_t r = orc_random_word(seed, worker, ORC_DOMAIN_NAT, index_offset + i);
+            uint32_t r = orc_random_word(seed, worker, domain, index_offset + i);
             exp_out[i] = (uint8_t)orc_nat_round(u, r);
             sb |= (uint8_t)((u >> 31) << bit);
         }
         sign_out[byte] = sb;
     }
+}
+
+void orc_nat_encode(const float *x, uint64_t d, uint64_t seed, uint32_t worker,
+                    uint64_t index_offset, uint8_t *exp_out, uint8_t *sign_out)
+{
+    nat_encode_domain(x, d, seed, worker, ORC_DOMAIN_NAT, index_offset, exp_out, sign_out);
 }
 
 /* The decoded value has the stored sign and exponent and a zero mantissa. */
@@ -539,4 +545,21 @@ void orc_sparse_nat_aggregate(const uint32_t *idx, uint64_t idx_stride, const ui
             if (abs64) abs64[i] += fabs((double)v);
         }
     }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Master-side compression                                                  */
+/* ------------------------------------------------------------------------ */
+
+/* Algorithm 1, master: Delta = sum over workers of the decompressed updates,
+ * then g = C_M(Delta) with C_M = C_nat (bidirectional compression; the master's
+ * draws come from their own stream, domain 3, keyed by `master` instead of a
+ * worker id).  The sum is the binary32 left-to-right sum of orc_aggregate_nat.
+ * `sum32` is caller scratch of d floats (it receives Delta). */
+void orc_master_nat(const uint8_t *exp, uint64_t exp_stride, const uint8_t *sign, uint64_t sign_stride,
+                    uint32_t n, uint64_t d, uint64_t seed, uint32_t master, uint64_t index_offset,
+                    float *sum32, uint8_t *exp_out, uint8_t *sign_out)
+{
+    orc_aggregate_nat(exp, exp_stride, sign, sign_stride, n, d, NULL, sum32, NULL);
+    nat_encode_domain(sum32, d, seed, master, ORC_DOMAIN_MASTER, index_offset, exp_out, sign_out);
 }

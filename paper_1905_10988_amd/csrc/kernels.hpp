@@ -80,6 +80,11 @@ hipError_t launch_sparse_nat_aggregate(const uint32_t* idx, size_t idx_stride, c
                                        const uint8_t* sign, size_t sign_stride, uint32_t n, uint64_t k, uint64_t d,
                                        float* out, bool out_aligned, hipStream_t stream);
 
+struct NatMasterArgs {
+    uint32_t k0, k1, master; uint64_t index_offset; uint8_t* exp_out; uint8_t* sign_out;
+};
+hipError_t launch_nat_master(const NatAggregateArgs& a, const NatMasterArgs& m, bool fast, hipStream_t stream);
+
 // `fast` promises the alignment the vector path needs (checked by the caller).
 hipError_t launch_nat_encode(const NatEncodeArgs& a, uint32_t n, bool fast, hipStream_t stream);
 hipError_t launch_nat_decode(const NatDecodeArgs& a, bool fast, hipStream_t stream);

@@ -241,6 +241,63 @@ __global__ __launch_bounds__(kBlock) void nat_aggregate_kernel(NatAggregateArgs 
     }
 }
 
+// Master step of Algorithm 1 with C_M = C_nat: the same sum, then natural compression of the
+// sum with the master's own stream (domain 3, keyed by the master id), so 1.125 bytes leave per
+// element instead of 4.  Requires the aggregate kernel's alignment, exp_out 8-byte aligned and
+// index_offset a multiple of 4.
+__global__ __launch_bounds__(kBlock) void nat_master_kernel(NatAggregateArgs a, NatMasterArgs m) {
+    const uint64_t grp = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t full = a.d >> 3;
+    if (grp < full) {
+        float acc[8] = {-0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f};
+        uint32_t w0 = 0;
+        for (; w0 + 8 <= a.n; w0 += 8) nat_sum_chunk<8>(a, grp, w0, acc);
+        for (; w0 + 2 <= a.n; w0 += 2) nat_sum_chunk<2>(a, grp, w0, acc);
+        if (w0 < a.n) nat_sum_chunk<1>(a, grp, w0, acc);
+        uint32_t r0[4], r1[4];
+        const uint64_t q = (m.index_offset >> 2) + 2 * grp;
+        random_words4<true>(q, m.master, kDomainMaster, m.k0, m.k1, r0);
+        random_words4<true>(q + 1, m.master, kDomainMaster, m.k0, m.k1, r1);
+        uint32_t u[8], sb;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) u[j] = f32_bits(acc[j]);
+        sb = u[7] >> 31;
+#pragma unroll
+        for (int j = 6; j >= 0; --j) sb = push_sign(sb, u[j]);
+        u32x2 e;
+        e.x = pack_top_bytes(nat_round_top(u[0], r0[0]), nat_round_top(u[1], r0[1]), nat_round_top(u[2], r0[2]),
+                             nat_round_top(u[3], r0[3]));
+        e.y = pack_top_bytes(nat_round_top(u[4], r1[0]), nat_round_top(u[5], r1[1]), nat_round_top(u[6], r1[2]),
+                             nat_round_top(u[7], r1[3]));
+        store_stream(reinterpret_cast<u32x2*>(m.exp_out) + grp, e);
+        store_stream(m.sign_out + grp, (uint8_t)sb);
+    } else if (grp == full && (a.d & 7)) {
+        uint32_t sb = 0;
+        for (uint64_t i = grp * 8; i < a.d; ++i) {
+            const uint32_t u = f32_bits(nat_sum_one(a, i));
+            const uint32_t r = random_word(m.index_offset + i, m.master, kDomainMaster, m.k0, m.k1);
+            m.exp_out[i] = (uint8_t)(nat_round_top(u, ~r) >> 24);
+            sb |= (u >> 31) << (i & 7);
+        }
+        m.sign_out[grp] = (uint8_t)sb;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void nat_master_generic_kernel(NatAggregateArgs a, NatMasterArgs m) {
+    const uint64_t i0 = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 8;
+    if (i0 >= a.d) return;
+    uint32_t sb = 0;
+    for (int j = 0; j < 8; ++j) {
+        const uint64_t i = i0 + j;
+        if (i >= a.d) break;
+        const uint32_t u = f32_bits(nat_sum_one(a, i));
+        const uint32_t r = random_word(m.index_offset + i, m.master, kDomainMaster, m.k0, m.k1);
+        m.exp_out[i] = (uint8_t)(nat_round_top(u, ~r) >> 24);
+        sb |= (u >> 31) << j;
+    }
+    m.sign_out[i0 >> 3] = (uint8_t)sb;
+}
+
 __global__ __launch_bounds__(kBlock) void nat_aggregate_generic_kernel(NatAggregateArgs a) {
     const uint64_t i0 = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 8;
     for (int j = 0; j < 8; ++j) {
@@ -277,6 +334,13 @@ hipError_t launch_nat_aggregate(const NatAggregateArgs& a, bool fast, hipStream_
     const dim3 grid = grid_for_groups(a.d, 1);
     if (fast) nat_aggregate_kernel<<<grid, kBlock, 0, stream>>>(a);
     else nat_aggregate_generic_kernel<<<grid, kBlock, 0, stream>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_nat_master(const NatAggregateArgs& a, const NatMasterArgs& m, bool fast, hipStream_t stream) {
+    const dim3 grid = grid_for_groups(a.d, 1);
+    if (fast) nat_master_kernel<<<grid, kBlock, 0, stream>>>(a, m);
+    else nat_master_generic_kernel<<<grid, kBlock, 0, stream>>>(a, m);
     return hipGetLastError();
 }
 

@@ -211,6 +211,21 @@ nc_status nc_sparse_nat_aggregate(const uint32_t* idx, size_t idx_stride, const 
                                                 aligned(out, 16), (hipStream_t)stream));
 }
 
+nc_status nc_master_nat(const nc_agg_desc* desc, uint64_t seed, uint32_t master, uint64_t index_offset,
+                        uint8_t* exp_out, uint8_t* sign_out, void* stream) {
+    if (!desc) return NC_ERR_NULL;
+    if (desc->n == 0 || desc->d > kMaxD || desc->kind != NC_KIND_NAT) return NC_ERR_INVALID;
+    if (desc->d == 0) return NC_OK;
+    if (!desc->code || !desc->sign || !exp_out || !sign_out) return NC_ERR_NULL;
+    if (desc->n > 1 && (desc->code_stride < nc_nat_exp_bytes(desc->d) || desc->sign_stride < nc_sign_bytes(desc->d)))
+        return NC_ERR_INVALID;
+    NatAggregateArgs a{desc->code, desc->code_stride, desc->sign, desc->sign_stride, desc->n, desc->d, nullptr};
+    NatMasterArgs m{(uint32_t)seed, (uint32_t)(seed >> 32), master, index_offset, exp_out, sign_out};
+    const bool fast = aligned(desc->code, 8) && (desc->n == 1 || (desc->code_stride & 7) == 0) && aligned(exp_out, 8) &&
+                      (index_offset & 3) == 0;
+    return from_hip(launch_nat_master(a, m, fast, (hipStream_t)stream));
+}
+
 nc_status nc_aggregate_sum(const nc_agg_desc* desc, float* out, void* stream) {
     if (!desc) return NC_ERR_NULL;
     if (desc->n == 0 || desc->d > kMaxD) return NC_ERR_INVALID;

@@ -69,6 +69,8 @@ def lib():
         L.nc_sparse_nat_encode_batch.argtypes = [_vp, _sz, _u32, _u64, _u64, ctypes.c_float, _u64, _u32, _vp, _sz,
                                                  _vp, _sz, _vp, _sz, _vp]
         L.nc_sparse_nat_aggregate.argtypes = [_vp, _sz, _vp, _sz, _vp, _sz, _u32, _u64, _u64, _vp, _vp]
+        L.nc_master_nat.argtypes = [ctypes.POINTER(AggDesc), _u64, _u32, _u64, _vp, _vp, _vp]
+        L.nc_master_nat.restype = ctypes.c_int
         for name in ("nc_sparse_nat_encode", "nc_sparse_nat_encode_batch", "nc_sparse_nat_aggregate"):
             getattr(L, name).restype = ctypes.c_int
         for name in ("nc_nat_encode", "nc_nat_encode_batch", "nc_nat_decode", "nc_dither_encode",
@@ -307,6 +309,26 @@ def sparse_nat_aggregate(idx, exp, sign, k, d, out=None):
     _check(lib().nc_sparse_nat_aggregate(_ptr(idx), idx.shape[1], _ptr(exp), exp.shape[1], _ptr(sign), sign.shape[1],
                                          n, k, d, _ptr(out), _stream()))
     return out
+
+
+def master_nat(d, exp, sign, seed, master=0, index_offset=0, exp_out=None, sign_out=None):
+    """nc_master_nat over the rows of 2-D plane tensors: returns (exponent plane, sign plane) of C_nat(sum)."""
+    exp = _dev(exp, torch.uint8, "exp")
+    sign = _dev(sign, torch.uint8, "sign")
+    assert exp.dim() == 2 and sign.dim() == 2 and sign.shape[0] == exp.shape[0]
+    desc = AggDesc()
+    desc.kind, desc.n, desc.d = NC_KIND_NAT, exp.shape[0], d
+    desc.code, desc.code_stride = exp.data_ptr(), exp.shape[1]
+    desc.sign, desc.sign_stride = sign.data_ptr(), sign.shape[1]
+    if exp_out is None:
+        exp_out = torch.empty(nat_exp_bytes(d), dtype=torch.uint8, device=exp.device)
+    if sign_out is None:
+        sign_out = torch.empty(sign_bytes(d), dtype=torch.uint8, device=exp.device)
+    _dev(exp_out, torch.uint8, "exp_out")
+    _dev(sign_out, torch.uint8, "sign_out")
+    assert exp_out.numel() >= nat_exp_bytes(d) and sign_out.numel() >= sign_bytes(d)
+    _check(lib().nc_master_nat(ctypes.byref(desc), seed, master, index_offset, _ptr(exp_out), _ptr(sign_out), _stream()))
+    return exp_out, sign_out
 
 
 def p_value(p):

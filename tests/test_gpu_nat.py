@@ -197,3 +197,38 @@ def test_config2_full_size(nc, oracle, wl):
         np.stack([oracle.nat_encode(xs[w][a:], 0, w, index_offset=a)[0] for w in range(n)]),
         np.stack([oracle.nat_encode(xs[w][a:], 0, w, index_offset=a)[1] for w in range(n)]), 40)
     assert np.array_equal(got[a:].view(np.uint32), o32.view(np.uint32))
+
+
+@pytest.mark.parametrize("n,d,index_offset", [(1, 5, 0), (2, 4099, 0), (8, 65536, 4), (8, 70001, 2**34 + 8), (9, 1003, 3),
+                                              (17, 20000, 0)])
+def test_master_compression(nc, oracle, wl, n, d, index_offset):
+    """Fused sum + C_nat of the sum (Algorithm 1's master step): planes bit-exact with the oracle."""
+    x = np.stack([wl.config1(d=max(d, 2000), seed=60 + w)[:d] * np.float32(3.0 ** w) for w in range(n)])
+    exp, sign = nc.nat_encode_batch(dev(x), seed=5)
+    e_buf, s_buf = Guarded(nc.nat_exp_bytes(d)), Guarded(nc.sign_bytes(d))
+    nc.master_nat(d, exp, sign, seed=77, master=2, index_offset=index_offset, exp_out=e_buf.t, sign_out=s_buf.t)
+    torch.cuda.synchronize()
+    total, eo, so = oracle.master_nat(host(exp), host(sign), d, 77, 2, index_offset)
+    assert np.array_equal(e_buf.check(), eo)
+    assert np.array_equal(s_buf.check(), so)
+    assert np.array_equal(host(nc.aggregate_sum(nc.NC_KIND_NAT, d, exp, sign)).view(np.uint32), total.view(np.uint32))
+
+
+def test_master_compression_config2_full_size(nc, oracle, wl):
+    d, n = wl.D_RESNET50, wl.NUM_WORKERS
+    off = wl.layer_offsets()
+    row = (d + 63) // 64 * 64
+    xdev = torch.empty((n, row), dtype=torch.float32, device="cuda")
+    for w in range(n):
+        xdev[w, :d] = torch.from_numpy(wl.layered_gaussian(w, off)).cuda()
+    exp, sign = nc.nat_encode_batch(xdev, seed=0, d=d)
+    e, s = nc.master_nat(d, exp, sign, seed=1, master=0)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    eh, sh = host(e), host(s)
+    for a in [0, d - 4096] + (rng.integers(0, (d - 4096) // 8, 5) * 8).tolist():
+        b = a + 4096
+        ew = host(exp[:, a:b]).copy()
+        sw = host(sign[:, a // 8: b // 8]).copy()
+        _, eo, so = oracle.master_nat(ew, sw, b - a, 1, 0, index_offset=a)
+        assert np.array_equal(eh[a:b], eo) and np.array_equal(sh[a // 8: b // 8], so)

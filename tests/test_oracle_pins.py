@@ -538,3 +538,42 @@ def test_aggregate_against_numpy(oracle):
         for w in range(1, n):
             seq = (seq + dec[w]).astype(np.float32)
         assert np.array_equal(o32, seq)
+
+
+# ------------------------------------------------------------------ master-side compression
+def test_master_compression_is_cnat_of_the_sum(oracle):
+    """Algorithm 1's master step g = C_M(sum of decompressed updates) with C_M = C_nat: the output
+    brackets the sum element-wise, leaves sums that are powers of two (or zero) unchanged, uses a
+    stream of its own, and over seeds its mean is the sum (unbiased, composition theorem)."""
+    from paper_1905_10988_amd import workloads
+    d, n = 3001, 8
+    off = workloads.layer_offsets(d=d, num_layers=5, lo=64, hi=2000, seed=3)
+    planes = [oracle.nat_encode(workloads.layered_gaussian(w, off, seed=50), 4, w) for w in range(n)]
+    exp = np.stack([p[0] for p in planes])
+    sign = np.stack([p[1] for p in planes])
+    _, o32, _ = oracle.aggregate_nat(exp, sign, d)
+    total, e, s = oracle.master_nat(exp, sign, d, seed=4, master=0)
+    assert np.array_equal(total.view(np.uint32), o32.view(np.uint32))
+    g = oracle.nat_decode(e, s, d).astype(np.float64)
+    t = total.astype(np.float64)
+    nz = t != 0
+    lo = np.exp2(np.floor(np.log2(np.abs(t[nz]))))
+    assert np.all((np.abs(g[nz]) == lo) | (np.abs(g[nz]) == 2 * lo))
+    assert np.array_equal(np.signbit(g), np.signbit(t))
+    pow2 = nz & (np.frexp(np.abs(t))[0] == 0.5)
+    assert pow2.sum() > 50 and np.array_equal(g[pow2], t[pow2])
+    assert np.all(g[~nz] == 0)
+    # the master's words are not the workers' (domain 3 vs 0): re-encoding the sum as worker 0 differs
+    e_w, _ = oracle.nat_encode(total, 4, 0)
+    assert 0.05 < np.mean(e_w != e) < 0.6
+    # element i's code depends on its global index: slices with an offset agree
+    _, e2, s2 = oracle.master_nat(exp[:, 1000:2000].copy(), np.stack([np.packbits(np.unpackbits(r, bitorder="little")[1000:2000], bitorder="little") for r in sign]), 1000, seed=4, master=0, index_offset=1000)
+    assert np.array_equal(e2, e[1000:2000])
+    # unbiased over the master's seeds
+    S = 400
+    acc = np.zeros(d)
+    for seed in range(S):
+        _, ee, ss = oracle.master_nat(exp, sign, d, seed=1000 + seed, master=1)
+        acc += oracle.nat_decode(ee, ss, d)
+    se = np.abs(t) * math.sqrt(1 / 8 / S)
+    assert np.all(np.abs(acc / S - t) <= 5 * se + 1e-300)
