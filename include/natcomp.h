@@ -16,7 +16,7 @@
  *     g = index_offset + i of the stream (seed, worker, operator): output word (g mod 4)
  *     of Philox-4x32-10 with key = (lo32(seed), hi32(seed)) and counter =
  *     (lo32(g/4), hi32(g/4), worker, domain), domain 0 for C_nat, 1 for D_nat, 2 for the
- *     sparsifier's index selection and 3 for the master's C_nat.
+ *     sparsifier's index selection, 3 for the master's C_nat and 4 for compressed norms.
  *     Results therefore do not depend on how a vector is split into calls or launches.
  *
  * Plane layouts (little-endian bit order inside a byte):
@@ -129,6 +129,16 @@ nc_status nc_dither_encode(const float *x, uint64_t d, const uint64_t *seg_offse
 nc_status nc_dither_decode(const float *norms, const uint8_t *code, const uint8_t *sign, uint64_t d,
                            const uint64_t *seg_offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
                            float *out, void *stream);
+
+/* Naturally compressed norms (Sec. 3: general dithering with C = C_nat on the norm, 8 bits per
+ * norm; multiplying a level by such a norm is an exponent addition, at the price of a factor
+ * 9/8 in the second moment).  Each non-negative norms[s] is rounded by C_nat with word s of a
+ * stream of its own (domain 4): exp_out[s] is its exponent byte and norms_q_out[s] the power of
+ * two it stands for, ready to be passed as `norms` to nc_dither_decode / nc_aggregate_sum.  The
+ * encoder keeps normalising by the exact norm, as Def. 3 prescribes.
+ *   norms, norms_q_out DEVICE count floats (may be the same array);  exp_out DEVICE count bytes. */
+nc_status nc_norm_compress(const float *norms, uint64_t count, uint64_t seed, uint32_t worker,
+                           uint8_t *exp_out, float *norms_q_out, void *stream);
 
 /* ----------------------------------------------------------------------------------------
  * Master-side aggregation (Algorithm 1: Delta = sum over workers of the decompressed

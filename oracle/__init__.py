@@ -78,6 +78,8 @@ def lib():
         L.orc_sparse_nat_aggregate.restype = None
         L.orc_master_nat.argtypes = [_u8p, _u64, _u8p, _u64, _u32, _u64, _u64, _u32, _u64, _f32p, _u8p, _u8p]
         L.orc_master_nat.restype = None
+        L.orc_norm_compress.argtypes = [_f32p, _u64, _u64, _u32, _u8p, _f32p]
+        L.orc_norm_compress.restype = None
         L.orc_threads.argtypes = []
         L.orc_threads.restype = ctypes.c_int
         _lib = L
@@ -324,3 +326,16 @@ def master_nat(exp, sign, d, seed, master=0, index_offset=0):
     lib().orc_master_nat(_ptr(exp, _u8p), exp.shape[1], _ptr(sign, _u8p), sign.shape[1], n, d, seed, master,
                          index_offset, _ptr(total, _f32p), _ptr(e, _u8p), _ptr(s, _u8p))
     return total, e, s
+
+
+# ------------------------------------------------------------------ compressed norm
+DOMAIN_NORM = 4
+
+
+def norm_compress(norms, seed, worker=0):
+    """C_nat of every (non-negative) norm: (exponent bytes, the powers of two they stand for)."""
+    norms = _c(norms, np.float32)
+    e = np.zeros(norms.size, np.uint8)
+    q = np.zeros(norms.size, np.float32)
+    lib().orc_norm_compress(_ptr(norms, _f32p), norms.size, seed, worker, _ptr(e, _u8p), _ptr(q, _f32p))
+    return e, q

@@ -72,7 +72,7 @@ void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t ou
 }
 
 /* Domains keep the streams of different operators apart. */
-enum { ORC_DOMAIN_NAT = 0, ORC_DOMAIN_DITHER = 1, ORC_DOMAIN_MASTER = 3 };
+enum { ORC_DOMAIN_NAT = 0, ORC_DOMAIN_DITHER = 1, ORC_DOMAIN_MASTER = 3, ORC_DOMAIN_NORM = 4 };
 
 /* The 32-bit uniform word of global element g: the counter is (g/4, worker,
  * domain), the key is the seed, and the element takes output word g mod 4.
@@ -562,4 +562,25 @@ void orc_master_nat(const uint8_t *exp, uint64_t exp_stride, const uint8_t *sign
 {
     orc_aggregate_nat(exp, exp_stride, sign, sign_stride, n, d, NULL, sum32, NULL);
     nat_encode_domain(sum32, d, seed, master, ORC_DOMAIN_MASTER, index_offset, exp_out, sign_out);
+}
+
+/* ------------------------------------------------------------------------ */
+/* Compressed norm                                                          */
+/* ------------------------------------------------------------------------ */
+
+/* General dithering sends C(||x||_p); with C = C_nat the norm is a power of two
+ * (8 bits on the wire) and multiplying a level by it is an exponent addition
+ * (Sec. 3).  norm s of a worker draws the word of index s in a stream of its own
+ * (domain 4).  exp_out[s] = exponent byte, q_out[s] = the power of two it stands
+ * for (norms are non-negative: no sign is kept). */
+void orc_norm_compress(const float *norms, uint64_t count, uint64_t seed, uint32_t worker,
+                       uint8_t *exp_out, float *q_out)
+{
+    for (uint64_t s = 0; s < count; ++s) {
+        uint32_t u = f32_bits(norms[s]) & 0x7FFFFFFFu;
+        uint32_t r = orc_random_word(seed, worker, ORC_DOMAIN_NORM, s);
+        uint32_t e = orc_nat_round(u, r);
+        exp_out[s] = (uint8_t)e;
+        q_out[s] = bits_f32(e << 23);
+    }
 }

@@ -9,6 +9,7 @@ namespace natcomp {
 
 constexpr uint32_t kDomainNat = 0;     // C_nat stream
 constexpr uint32_t kDomainDither = 1;  // D_nat stream
+constexpr uint32_t kDomainNorm = 4;    // C_nat of the dithering norms
 constexpr uint32_t kDomainMaster = 3;  // master-side C_nat stream (2 = index selection of the sparsifier)
 
 constexpr uint32_t kPhiloxM0 = 0xD2511F53u, kPhiloxM1 = 0xCD9E8D57u;

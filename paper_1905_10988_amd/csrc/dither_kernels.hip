@@ -723,6 +723,30 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
     }
 }
 
+// ------------------------------------------------------------------------ compressed norm
+// C_nat of every norm (Sec. 3: general dithering with C = C_nat sends the norm as a power of
+// two): the exponent byte and the power of two it stands for.  Norms are non-negative, so
+// no sign is kept; norm s draws word s of its own stream (domain 4).
+__global__ __launch_bounds__(kBlock) void norm_compress_kernel(const float* __restrict__ norms, uint64_t count,
+                                                               uint32_t k0, uint32_t k1, uint32_t worker,
+                                                               uint8_t* __restrict__ exp_out,
+                                                               float* __restrict__ q_out) {
+    const uint64_t s = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (s >= count) return;
+    const uint32_t u = f32_bits(norms[s]) & 0x7FFFFFFFu;
+    const uint32_t r = random_word(s, worker, kDomainNorm, k0, k1);
+    const uint32_t e = add_sat(u << 1, (~r) >> 8) >> 24;  // exponent + [r < m 2^9], 255 absorbing
+    exp_out[s] = (uint8_t)e;
+    q_out[s] = bits_f32(e << 23);
+}
+
+hipError_t launch_norm_compress(const float* norms, uint64_t count, uint32_t k0, uint32_t k1, uint32_t worker,
+                                uint8_t* exp_out, float* q_out, hipStream_t stream) {
+    norm_compress_kernel<<<(unsigned)((count + kBlock - 1) / kBlock), kBlock, 0, stream>>>(norms, count, k0, k1, worker,
+                                                                                          exp_out, q_out);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------ launchers
 template <int BLOCK, bool FAST>
 static hipError_t launch_bucket(const DitherEncodeArgs& a, unsigned grid, hipStream_t st) {

@@ -80,6 +80,9 @@ hipError_t launch_sparse_nat_aggregate(const uint32_t* idx, size_t idx_stride, c
                                        const uint8_t* sign, size_t sign_stride, uint32_t n, uint64_t k, uint64_t d,
                                        float* out, bool out_aligned, hipStream_t stream);
 
+hipError_t launch_norm_compress(const float* norms, uint64_t count, uint32_t k0, uint32_t k1, uint32_t worker,
+                                uint8_t* exp_out, float* q_out, hipStream_t stream);
+
 struct NatMasterArgs {
     uint32_t k0, k1, master; uint64_t index_offset; uint8_t* exp_out; uint8_t* sign_out;
 };

@@ -211,6 +211,15 @@ nc_status nc_sparse_nat_aggregate(const uint32_t* idx, size_t idx_stride, const 
                                                 aligned(out, 16), (hipStream_t)stream));
 }
 
+nc_status nc_norm_compress(const float* norms, uint64_t count, uint64_t seed, uint32_t worker, uint8_t* exp_out,
+                           float* norms_q_out, void* stream) {
+    if (count >= (1ull << 31) * kBlock) return NC_ERR_INVALID;
+    if (count == 0) return NC_OK;
+    if (!norms || !exp_out || !norms_q_out) return NC_ERR_NULL;
+    return from_hip(launch_norm_compress(norms, count, (uint32_t)seed, (uint32_t)(seed >> 32), worker, exp_out,
+                                         norms_q_out, (hipStream_t)stream));
+}
+
 nc_status nc_master_nat(const nc_agg_desc* desc, uint64_t seed, uint32_t master, uint64_t index_offset,
                         uint8_t* exp_out, uint8_t* sign_out, void* stream) {
     if (!desc) return NC_ERR_NULL;

@@ -69,6 +69,8 @@ def lib():
         L.nc_sparse_nat_encode_batch.argtypes = [_vp, _sz, _u32, _u64, _u64, ctypes.c_float, _u64, _u32, _vp, _sz,
                                                  _vp, _sz, _vp, _sz, _vp]
         L.nc_sparse_nat_aggregate.argtypes = [_vp, _sz, _vp, _sz, _vp, _sz, _u32, _u64, _u64, _vp, _vp]
+        L.nc_norm_compress.argtypes = [_vp, _u64, _u64, _u32, _vp, _vp, _vp]
+        L.nc_norm_compress.restype = ctypes.c_int
         L.nc_master_nat.argtypes = [ctypes.POINTER(AggDesc), _u64, _u32, _u64, _vp, _vp, _vp]
         L.nc_master_nat.restype = ctypes.c_int
         for name in ("nc_sparse_nat_encode", "nc_sparse_nat_encode_batch", "nc_sparse_nat_aggregate"):
@@ -309,6 +311,15 @@ def sparse_nat_aggregate(idx, exp, sign, k, d, out=None):
     _check(lib().nc_sparse_nat_aggregate(_ptr(idx), idx.shape[1], _ptr(exp), exp.shape[1], _ptr(sign), sign.shape[1],
                                          n, k, d, _ptr(out), _stream()))
     return out
+
+
+def norm_compress(norms, seed, worker=0):
+    """nc_norm_compress: (exponent bytes, power-of-two norms)."""
+    norms = _dev(norms, torch.float32, "norms")
+    e = torch.empty(norms.numel(), dtype=torch.uint8, device=norms.device)
+    q = torch.empty(norms.numel(), dtype=torch.float32, device=norms.device)
+    _check(lib().nc_norm_compress(_ptr(norms), norms.numel(), seed, worker, _ptr(e), _ptr(q), _stream()))
+    return e, q
 
 
 def master_nat(d, exp, sign, seed, master=0, index_offset=0, exp_out=None, sign_out=None):

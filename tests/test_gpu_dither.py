@@ -269,3 +269,23 @@ def test_config4_full_size_two_workers(nc, oracle, wl):
         o64, o32, oa = oracle.aggregate_dither(norms_h[:, b:b + 1].copy(), cw, None, a1 - a0, s)
         assert np.array_equal(got[a0:a1].view(np.uint32), o32.view(np.uint32))
         assert np.all(np.abs(got[a0:a1].astype(np.float64) - o64) <= 1e-5 * oa)
+
+
+def test_compressed_norm(nc, oracle, wl):
+    """C_nat on the norms (Sec. 3): exponent bytes and power-of-two norms bit-exact with the oracle,
+    and decoding with them (an exponent addition) equals the oracle's decode."""
+    d, bucket, s = 100_003, 512, 8
+    x = wl.bucketed_gaussian(0, d=d, bucket=bucket, seed=23)
+    norms, code, sign = nc.dither_encode(dev(x), 2, s, 5, worker=3, bucket=bucket)
+    e, q = nc.norm_compress(norms, seed=5, worker=3)
+    y = nc.dither_decode(q, code, sign, d, s, bucket=bucket)
+    torch.cuda.synchronize()
+    eo, qo = oracle.norm_compress(host(norms), 5, 3)
+    assert np.array_equal(host(e), eo) and np.array_equal(host(q).view(np.uint32), qo.view(np.uint32))
+    assert 0.1 < np.mean(host(q) > host(norms)) < 0.9
+    yo = oracle.dither_decode(qo, host(code), host(sign), d, s, bucket=bucket)
+    assert np.array_equal(host(y).view(np.uint32), yo.view(np.uint32))
+    edge = np.array([0.0, 1.0, 3e-39, 3.4e38, np.inf, 0.75], np.float32)
+    e2, q2 = nc.norm_compress(dev(edge), seed=1)
+    eo2, qo2 = oracle.norm_compress(edge, 1)
+    assert np.array_equal(host(e2), eo2) and np.array_equal(host(q2).view(np.uint32), qo2.view(np.uint32))

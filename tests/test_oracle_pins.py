@@ -577,3 +577,36 @@ def test_master_compression_is_cnat_of_the_sum(oracle):
         acc += oracle.nat_decode(ee, ss, d)
     se = np.abs(t) * math.sqrt(1 / 8 / S)
     assert np.all(np.abs(acc / S - t) <= 5 * se + 1e-300)
+
+
+# ------------------------------------------------------------------ compressed norm
+def test_dithering_with_naturally_compressed_norm(oracle):
+    """General dithering with C = C_nat on the norm (Sec. 3): the sent norm is one of the two powers
+    of two around the true norm (unchanged if it already is one), the operator stays unbiased and
+    its second moment grows by at most the factor 9/8."""
+    rng = np.random.default_rng(41)
+    d, s, p, S = 4000, 6, 2, 600
+    x = rng.standard_normal(d).astype(np.float32)
+    x64 = x.astype(np.float64)
+    norms = oracle.pnorm_segments(x, p, bucket=500).astype(np.float32)
+    e, q = oracle.norm_compress(norms, seed=3)
+    lo = np.exp2(np.floor(np.log2(norms.astype(np.float64))))
+    assert np.all((q == lo) | (q == 2 * lo))
+    assert np.array_equal(e, (q.view(np.uint32) >> 23).astype(np.uint8))
+    e2, q2 = oracle.norm_compress(np.array([4.0, 0.0, 0.5], np.float32), seed=9)
+    assert q2.tolist() == [4.0, 0.0, 0.5]
+    acc = np.zeros(d)
+    second = 0.0
+    for seed in range(S):
+        code, sign = oracle.dither_encode(x, s, norms, seed, bucket=500)       # y uses the exact norm
+        _, qn = oracle.norm_compress(norms, seed)
+        y = oracle.dither_decode(qn, code, sign, d, s, bucket=500).astype(np.float64)
+        acc += y
+        second += (y ** 2).sum()
+    a = 500 ** 0.5 * 2.0 ** (1 - s)
+    omega = 1 / 8 + a * min(1.0, a)                      # Thm. 4 with the bucket length as d
+    assert second / S <= (9 / 8) * (omega + 1) * (x64 ** 2).sum()
+    var = second / S - (x64 ** 2).sum()
+    sd = math.sqrt(max(var, 0) / d / S)
+    assert abs((acc / S - x64).mean()) < 5 * sd / math.sqrt(d)
+    assert np.abs(acc / S - x64).max() < 10 * float(norms.max()) / math.sqrt(S)
