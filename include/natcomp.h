@@ -58,7 +58,7 @@ const char *nc_status_string(nc_status st);
  * -------------------------------------------------------------------------------------- */
 size_t nc_nat_exp_bytes(uint64_t d);                   /* d */
 size_t nc_sign_bytes(uint64_t d);                      /* ceil(d/8) */
-size_t nc_dither_code_bytes(uint64_t d, uint32_t s);   /* ceil(d/2) for s <= 15, else d; 0 if s is invalid */
+size_t nc_dither_code_bytes(uint64_t d, uint32_t s);   /* ceil(d/2) for s <= 15, else d; 0 if s is outside 1..255 */
 size_t nc_dither_sign_bytes(uint64_t d, uint32_t s);   /* 0 for s <= 7, else ceil(d/8) */
 /* Suggested distance between the planes of consecutive workers: bytes rounded up to 256. */
 size_t nc_plane_stride(size_t bytes);
@@ -130,6 +130,21 @@ nc_status nc_dither_decode(const float *norms, const uint8_t *code, const uint8_
                            const uint64_t *seg_offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
                            float *out, void *stream);
 
+/* Standard dithering D_sta^{p,s} (Def. 3 with the linear partition l = j/s and the norm sent
+ * uncompressed: the operator of QSGD and TernGrad), the comparison operator of the paper's
+ * empirical-variance study.  Same arguments, segments, planes and code formats as
+ * nc_dither_encode / nc_dither_decode (random words: the same stream, domain 1), with
+ * 1 <= s <= 255 and level code c in 0..s standing for c/s:
+ *   t = fl(y s) with y = fl(|x| fl(1/norm)); c = floor(t) + [r < floor((t - floor(t)) 2^32)];
+ *   t >= s gives c = s.  Decoded value: sign * fl(norm * fl(c / s)). */
+nc_status nc_dither_sta_encode(const float *x, uint64_t d, const uint64_t *seg_offsets, uint32_t num_segments,
+                               uint32_t bucket, float p, uint32_t s, uint64_t seed, uint32_t worker,
+                               uint64_t index_offset, float *norms_out, uint8_t *code_out, uint8_t *sign_out,
+                               void *workspace, size_t workspace_bytes, void *stream);
+nc_status nc_dither_sta_decode(const float *norms, const uint8_t *code, const uint8_t *sign, uint64_t d,
+                               const uint64_t *seg_offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
+                               float *out, void *stream);
+
 /* Naturally compressed norms (Sec. 3: general dithering with C = C_nat on the norm, 8 bits per
  * norm; multiplying a level by such a norm is an exponent addition, at the price of a factor
  * 9/8 in the second moment).  Each non-negative norms[s] is rounded by C_nat with word s of a
@@ -150,9 +165,10 @@ nc_status nc_norm_compress(const float *norms, uint64_t count, uint64_t seed, ui
  *   kind = NC_KIND_NAT:    code is the exponent plane; norms, s and the segment fields unused.
  *   kind = NC_KIND_DITHER: code/sign/norms as written by nc_dither_encode with the same s and
  *                          segment description; sign may be NULL when s <= 7.
+ *   kind = NC_KIND_DITHER_STA: the same for nc_dither_sta_encode.
  * out: DEVICE, d floats.  Fastest when strides are multiples of 16 and planes 16-byte aligned.
  * -------------------------------------------------------------------------------------- */
-enum { NC_KIND_NAT = 0, NC_KIND_DITHER = 1 };
+enum { NC_KIND_NAT = 0, NC_KIND_DITHER = 1, NC_KIND_DITHER_STA = 2 };
 
 typedef struct {
     int32_t kind;

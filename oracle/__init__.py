@@ -80,6 +80,14 @@ def lib():
         L.orc_master_nat.restype = None
         L.orc_norm_compress.argtypes = [_f32p, _u64, _u64, _u32, _u8p, _f32p]
         L.orc_norm_compress.restype = None
+        L.orc_sta_level.argtypes = [ctypes.c_float, _u32, _u32]
+        L.orc_sta_level.restype = _u32
+        L.orc_sta_count.argtypes = [ctypes.c_float, _u32, _u32]
+        L.orc_sta_count.restype = _u64
+        L.orc_sta_encode.argtypes = L.orc_dither_encode.argtypes
+        L.orc_sta_encode.restype = None
+        L.orc_sta_decode.argtypes = L.orc_dither_decode.argtypes
+        L.orc_sta_decode.restype = None
         L.orc_threads.argtypes = []
         L.orc_threads.restype = ctypes.c_int
         _lib = L
@@ -339,3 +347,40 @@ def norm_compress(norms, seed, worker=0):
     q = np.zeros(norms.size, np.float32)
     lib().orc_norm_compress(_ptr(norms, _f32p), norms.size, seed, worker, _ptr(e, _u8p), _ptr(q, _f32p))
     return e, q
+
+
+# ------------------------------------------------------------------ standard dithering
+def sta_level(y, s, r):
+    assert 1 <= s <= 255
+    return int(lib().orc_sta_level(np.float32(y), s, r))
+
+
+def sta_count(y, s, code):
+    assert 1 <= s <= 255
+    return int(lib().orc_sta_count(np.float32(y), s, code))
+
+
+def sta_encode(x, s, norms, seed, worker=0, index_offset=0, offsets=None, bucket=0):
+    assert 1 <= s <= 255
+    x = _c(x, np.float32)
+    d = x.size
+    off, nseg, bucket, count = _segs(d, offsets, bucket)
+    norms = _c(norms, np.float32)
+    assert norms.size == count
+    code = np.zeros(dither_code_bytes(d, s), np.uint8)
+    sign = np.zeros(max(dither_sign_bytes(d, s), 1), np.uint8)
+    lib().orc_sta_encode(_ptr(x, _f32p), d, _ptr(off, _u64p), nseg, bucket, s, _ptr(norms, _f32p), seed, worker,
+                         index_offset, _ptr(code, _u8p), _ptr(sign, _u8p))
+    return code, sign[:dither_sign_bytes(d, s)]
+
+
+def sta_decode(norms, code, sign, d, s, offsets=None, bucket=0):
+    assert 1 <= s <= 255
+    off, nseg, bucket, count = _segs(d, offsets, bucket)
+    norms = _c(norms, np.float32)
+    code = _c(code, np.uint8)
+    sign = _c(sign, np.uint8) if dither_sign_bytes(d, s) else None
+    out = np.zeros(d, np.float32)
+    lib().orc_sta_decode(_ptr(norms, _f32p), _ptr(code, _u8p), _ptr(sign, _u8p), d, _ptr(off, _u64p), nseg, bucket,
+                         s, _ptr(out, _f32p))
+    return out

@@ -584,3 +584,76 @@ void orc_norm_compress(const float *norms, uint64_t count, uint64_t seed, uint32
         q_out[s] = bits_f32(e << 23);
     }
 }
+
+/* ------------------------------------------------------------------------ */
+/* Standard dithering (comparison operator)                                 */
+/* ------------------------------------------------------------------------ */
+
+/* Def. 3 with the linear partition l_j = j/s (standard dithering, the operator
+ * of QSGD and TernGrad) and the norm sent as it is.  Level code c in 0..s
+ * stands for c/s.  y lies between floor(ys)/s and (floor(ys)+1)/s and goes to
+ * the higher one with probability ys - floor(ys).  y is given as a binary32
+ * number; t = fl(y s) is one rounded product, t - floor(t) is exact, and the
+ * comparison with r/2^32 is the integer comparison r < floor(frac 2^32).
+ * t >= s (y >= 1, or a NaN) is the top level. */
+uint32_t orc_sta_level(float y, uint32_t s, uint32_t r)
+{
+    volatile float t = y * (float)s;
+    if (!(t < (float)s)) return s;
+    float fl = floorf(t);
+    float frac = t - fl;
+    uint64_t threshold = (uint64_t)(frac * 4294967296.0f);
+    return (uint32_t)fl + (((uint64_t)r < threshold) ? 1u : 0u);
+}
+
+uint64_t orc_sta_count(float y, uint32_t s, uint32_t code)
+{
+    uint64_t count = 0;
+#pragma omp parallel for reduction(+ : count)
+    for (int64_t r = 0; r < ((int64_t)1 << 32); ++r)
+        count += (orc_sta_level(y, s, (uint32_t)r) == code);
+    return count;
+}
+
+/* Same segments, normalisation (y = fl(|x| fl(1/norm))), random stream and packed
+ * layout as orc_dither_encode; 1 <= s <= 255. */
+void orc_sta_encode(const float *x, uint64_t d, const uint64_t *offsets, uint32_t num_segments,
+                    uint32_t bucket, uint32_t s, const float *norms, uint64_t seed, uint32_t worker,
+                    uint64_t index_offset, uint8_t *code_out, uint8_t *sign_out)
+{
+    memset(code_out, 0, orc_dither_code_bytes(d, s));
+    if (orc_dither_sign_bytes(d, s)) memset(sign_out, 0, orc_dither_sign_bytes(d, s));
+    uint64_t n = seg_count(d, offsets, num_segments, bucket);
+    for (uint64_t sgm = 0; sgm < n; ++sgm) {
+        uint64_t b = seg_begin(sgm, d, offsets, num_segments, bucket);
+        uint64_t e = seg_begin(sgm + 1, d, offsets, num_segments, bucket);
+        float inv = orc_dither_inv_norm(norms[sgm]);
+        for (uint64_t i = b; i < e; ++i) {
+            volatile float y = fabsf(x[i]) * inv;
+            uint32_t r = orc_random_word(seed, worker, ORC_DOMAIN_DITHER, index_offset + i);
+            put_code(code_out, sign_out, i, s, orc_sta_level(y, s, r), f32_bits(x[i]) >> 31);
+        }
+    }
+}
+
+/* sign * fl(norm * fl(c / s)), a signed zero for c = 0. */
+void orc_sta_decode(const float *norms, const uint8_t *code, const uint8_t *sign, uint64_t d,
+                    const uint64_t *offsets, uint32_t num_segments, uint32_t bucket, uint32_t s, float *out)
+{
+    uint64_t n = seg_count(d, offsets, num_segments, bucket);
+    for (uint64_t sgm = 0; sgm < n; ++sgm) {
+        uint64_t b = seg_begin(sgm, d, offsets, num_segments, bucket);
+        uint64_t e = seg_begin(sgm + 1, d, offsets, num_segments, bucket);
+        for (uint64_t i = b; i < e; ++i) {
+            uint32_t c, sg;
+            get_code(code, sign, i, s, &c, &sg);
+            float mag = 0.0f;
+            if (c > 0) {
+                volatile float level = (float)c / (float)s;
+                volatile float v = norms[sgm] * level;
+                mag = v;
+            }
+            out[i] = sg ? -mag : mag;
+        }
+    }
+}

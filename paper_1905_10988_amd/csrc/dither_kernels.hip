@@ -124,14 +124,18 @@ struct LevelParams {
     int32_t e_max;        // 127: exponent field of y = 1, the top level
     uint32_t regular_lo;  // (128 - s) << 23: bits of the lowest non-zero level 2^(1-s)
     float low_scale;      // 2^(s+31): y * low_scale = threshold of the linear region (s <= 95)
+    uint32_t standard;    // 1: standard dithering (levels j/s) instead of the natural level set
+    float s_float;        // s as a float (standard dithering)
 };
-__device__ __forceinline__ LevelParams level_params(uint32_t s) {
+__device__ __forceinline__ LevelParams level_params(uint32_t s, uint32_t standard) {
     LevelParams p;
     p.s = s;
+    p.standard = standard;
+    p.s_float = (float)s;
     p.e_min = 128 - (int32_t)s;
     p.e_max = 127;
     p.regular_lo = (uint32_t)(128 - s) << 23;
-    p.low_scale = (s <= 95) ? bits_f32((uint32_t)(127 + s + 31) << 23) : 0.0f;
+    p.low_scale = (s <= 95 && !standard) ? bits_f32((uint32_t)(127 + s + 31) << 23) : 0.0f;
     return p;
 }
 
@@ -170,6 +174,23 @@ __device__ __forceinline__ uint32_t dither_level(float x, float inv, uint32_t rc
         const uint32_t T = sh >= 32 ? 0u : ((0x80000000u | (m << 8)) >> sh);
         return r < T ? 1u : 0u;
     }
+}
+
+// Standard dithering (Def. 3 with the linear partition l = j/s, the QSGD / TernGrad operator,
+// kept as the comparison operator of the empirical-variance study): t = fl(y s) lies between
+// the levels floor(t)/s and (floor(t)+1)/s and goes up with probability t - floor(t), compared
+// as floor(frac 2^32) against the random word; y >= 1 (or a NaN) is the top level s.
+__device__ __forceinline__ uint32_t dither_level_standard(float x, float inv, uint32_t rc, const LevelParams& lp) {
+    const float y = fabsf(x) * inv;
+    const float t = y * lp.s_float;
+    if (!(t < lp.s_float)) return lp.s;
+    const float fl = floorf(t);
+    const float frac = t - fl;  // exact
+    uint32_t T;
+    asm("v_cvt_u32_f32 %0, %1" : "=v"(T) : "v"(frac * 4294967296.0f));  // exact: frac < 1 has 24 bits
+    uint32_t unused;
+    const bool below = __builtin_uadd_overflow(T, rc, &unused);  // r < T
+    return (uint32_t)fl + (below ? 1u : 0u);
 }
 
 // ------------------------------------------------------------------------ packing of 8 codes
@@ -247,8 +268,11 @@ __device__ __forceinline__ void encode_group(const DitherEncodeArgs& a, const ui
                                              uint64_t i0, uint32_t count) {
     uint32_t rc[8], c[8];
     words8<FAST>(a.index_offset + i0, a.worker, a.k0, a.k1, rc);
-    const LevelParams lp = level_params(a.s);
-    if (a.s <= 95) {
+    const LevelParams lp = level_params(a.s, a.standard);
+    if (a.standard) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) c[j] = dither_level_standard(bits_f32(u[j]), inv[j], rc[j], lp);
+    } else if (a.s <= 95) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) c[j] = dither_level<true>(bits_f32(u[j]), inv[j], rc[j], lp);
     } else {
@@ -262,7 +286,12 @@ __device__ __forceinline__ void encode_group(const DitherEncodeArgs& a, const ui
 // Level codes of one quad with a common reciprocal norm.
 __device__ __forceinline__ void levels4(u32x4 v, float inv, const uint32_t rc[4], const LevelParams& lp,
                                         uint32_t c[4]) {
-    if (lp.s <= 95) {
+    if (lp.standard) {
+        c[0] = dither_level_standard(bits_f32(v.x), inv, rc[0], lp);
+        c[1] = dither_level_standard(bits_f32(v.y), inv, rc[1], lp);
+        c[2] = dither_level_standard(bits_f32(v.z), inv, rc[2], lp);
+        c[3] = dither_level_standard(bits_f32(v.w), inv, rc[3], lp);
+    } else if (lp.s <= 95) {
         c[0] = dither_level<true>(bits_f32(v.x), inv, rc[0], lp);
         c[1] = dither_level<true>(bits_f32(v.y), inv, rc[1], lp);
         c[2] = dither_level<true>(bits_f32(v.z), inv, rc[2], lp);
@@ -364,7 +393,7 @@ void dither_bucket_encode_vec_kernel(DitherEncodeArgs a) {
     const float norm = norm_value(acc, a.pnorm);
     if (threadIdx.x == 0) a.norms_out[blockIdx.x] = norm;
     const float iv = inv_of_norm(norm);
-    const LevelParams lp = level_params(a.s);
+    const LevelParams lp = level_params(a.s, a.standard);
     const uint64_t q_global = (a.index_offset + begin) >> 2;
     uint32_t* __restrict__ code_base = reinterpret_cast<uint32_t*>(a.code_out + (FMT == kFmtByte ? begin : begin >> 1));
     uint32_t* __restrict__ sign_base = reinterpret_cast<uint32_t*>(a.sign_out + (begin >> 3));
@@ -531,7 +560,7 @@ __global__ __launch_bounds__(kBlock) void dither_segment_encode_kernel(DitherEnc
     uint32_t scalar_from = 0;                         // chunk-local element where the scalar part starts
     if (FAST && one_segment) {
         const float iv = a.inv_norm[s0];
-        const LevelParams lp = level_params(a.s);
+        const LevelParams lp = level_params(a.s, a.standard);
         const uint64_t q_global = (a.index_offset + cb) >> 2;
         uint32_t* __restrict__ code_base = reinterpret_cast<uint32_t*>(a.code_out + (FMT == kFmtByte ? cb : cb >> 1));
         uint32_t* __restrict__ sign_base = reinterpret_cast<uint32_t*>(a.sign_out + (cb >> 3));
@@ -572,8 +601,10 @@ __global__ __launch_bounds__(kBlock) void dither_segment_encode_kernel(DitherEnc
 
 // ------------------------------------------------------------------------ decode and sum
 // Value bits of (norm, code c, sign): sign | fl(norm * 2^(c-s)), a signed zero for c = 0.
-__device__ __forceinline__ float dither_value(float norm, uint32_t s, uint32_t c, uint32_t sign_bit) {
-    const float level = bits_f32((127u + c - s) << 23);  // 2^(c-s), normal for 1 <= c <= s <= 127
+__device__ __forceinline__ float dither_value(float norm, uint32_t s, uint32_t c, uint32_t sign_bit,
+                                              uint32_t standard) {
+    // natural: 2^(c-s), normal for 1 <= c <= s <= 127; standard: fl(c / s)
+    const float level = standard ? (float)c / (float)s : bits_f32((127u + c - s) << 23);
     const float mag = c ? norm * level : 0.0f;
     return bits_f32(f32_bits(mag) | (sign_bit << 31));
 }
@@ -626,7 +657,7 @@ __device__ __forceinline__ float dither_sum_one(const DitherAggregateArgs& a, ui
             if (FMT == kFmtFused) { c = nib & 7u; sgn = nib >> 3; }
             else { c = nib; sgn = (a.sign[(size_t)w * a.sign_stride + (i >> 3)] >> (i & 7)) & 1u; }
         }
-        acc += dither_value(a.norms[(size_t)w * a.norm_stride + seg], a.s, c, sgn);
+        acc += dither_value(a.norms[(size_t)w * a.norm_stride + seg], a.s, c, sgn, a.standard);
     }
     return acc;
 }
@@ -669,8 +700,8 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
                 const uint32_t w = threadIdx.x >> 4, nib = threadIdx.x & 15u;
                 if (w < nw) {
                     const float norm = a.norms[(size_t)(w0 + w) * a.norm_stride + s0];
-                    table[threadIdx.x] = (FMT == kFmtFused) ? dither_value(norm, a.s, nib & 7u, nib >> 3)
-                                                           : dither_value(norm, a.s, nib, 0u);
+                    table[threadIdx.x] = (FMT == kFmtFused) ? dither_value(norm, a.s, nib & 7u, nib >> 3, a.standard)
+                                                           : dither_value(norm, a.s, nib, 0u, a.standard);
                 }
             }
             __syncthreads();

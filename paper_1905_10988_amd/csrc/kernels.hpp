@@ -41,7 +41,7 @@ constexpr uint32_t kMaxOnePassBucket = 8192;  // largest bucket one workgroup ke
 
 struct DitherEncodeArgs {
     const float* x; Segs segs;
-    int pnorm; uint32_t s; int fmt;
+    int pnorm; uint32_t s; int fmt; uint32_t standard;   // standard = 1: levels j/s instead of 2^(j-s)
     uint32_t k0, k1, worker; uint64_t index_offset;
     float* norms_out; uint8_t* code_out; uint8_t* sign_out;
     double* first_partial;   // one per norm chunk (two-pass path only)
@@ -51,7 +51,7 @@ struct DitherEncodeArgs {
 struct DitherAggregateArgs {
     const float* norms; size_t norm_stride; const uint8_t* code; size_t code_stride;
     const uint8_t* sign; size_t sign_stride;
-    uint32_t n; Segs segs; uint32_t s; int fmt; float* out;
+    uint32_t n; Segs segs; uint32_t s; int fmt; uint32_t standard; float* out;
 };
 
 // One-pass encoder for fixed buckets of at most kMaxOnePassBucket elements (a multiple of 8).

@@ -16,7 +16,8 @@ constexpr uint64_t kMaxD = 1ull << 40;  // keeps every grid dimension below 2^31
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 inline nc_status from_hip(hipError_t e) { return e == hipSuccess ? NC_OK : NC_ERR_LAUNCH; }
 inline uint32_t code_width(uint32_t s) { uint32_t b = 0; while ((1u << b) < s + 1) ++b; return b; }
-inline bool valid_s(uint32_t s) { return s >= 1 && s <= 127; }
+inline bool valid_s(uint32_t s) { return s >= 1 && s <= 127; }       // natural levels: all normal numbers
+inline bool valid_s_size(uint32_t s) { return s >= 1 && s <= 255; }  // codes 0..s fit one byte
 
 }  // namespace
 
@@ -37,11 +38,11 @@ const char* nc_status_string(nc_status st) {
 size_t nc_nat_exp_bytes(uint64_t d) { return (size_t)d; }
 size_t nc_sign_bytes(uint64_t d) { return (size_t)((d + 7) / 8); }
 size_t nc_dither_code_bytes(uint64_t d, uint32_t s) {
-    if (!valid_s(s)) return 0;
+    if (!valid_s_size(s)) return 0;
     return code_width(s) <= 4 ? (size_t)((d + 1) / 2) : (size_t)d;
 }
 size_t nc_dither_sign_bytes(uint64_t d, uint32_t s) {
-    if (!valid_s(s)) return 0;
+    if (!valid_s_size(s)) return 0;
     return code_width(s) <= 3 ? 0 : (size_t)((d + 7) / 8);
 }
 size_t nc_plane_stride(size_t bytes) { return (bytes + 255) & ~(size_t)255; }
@@ -115,11 +116,11 @@ size_t nc_dither_workspace_bytes(uint64_t d, uint32_t num_segments, uint32_t buc
     return (size_t)(8 * chunks + 8 * nseg + align8(4 * nseg));
 }
 
-nc_status nc_dither_encode(const float* x, uint64_t d, const uint64_t* seg_offsets, uint32_t num_segments,
-                           uint32_t bucket, float p, uint32_t s, uint64_t seed, uint32_t worker,
-                           uint64_t index_offset, float* norms_out, uint8_t* code_out, uint8_t* sign_out,
-                           void* workspace, size_t workspace_bytes, void* stream) {
-    if (!valid_s(s) || d > kMaxD) return NC_ERR_INVALID;
+static nc_status dither_encode(uint32_t standard, const float* x, uint64_t d, const uint64_t* seg_offsets,
+                               uint32_t num_segments, uint32_t bucket, float p, uint32_t s, uint64_t seed,
+                               uint32_t worker, uint64_t index_offset, float* norms_out, uint8_t* code_out,
+                               uint8_t* sign_out, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!(standard ? valid_s_size(s) : valid_s(s)) || d > kMaxD) return NC_ERR_INVALID;
     int pnorm;
     if (p == 1.0f) pnorm = kNormL1;
     else if (p == 2.0f) pnorm = kNormL2;
@@ -132,7 +133,7 @@ nc_status nc_dither_encode(const float* x, uint64_t d, const uint64_t* seg_offse
     DitherEncodeArgs a{};
     nc_status st = check_segments(d, seg_offsets, num_segments, bucket, &a.segs);
     if (st != NC_OK) return st;
-    a.x = x; a.pnorm = pnorm; a.s = s; a.fmt = fmt;
+    a.x = x; a.pnorm = pnorm; a.s = s; a.fmt = fmt; a.standard = standard;
     a.k0 = (uint32_t)seed; a.k1 = (uint32_t)(seed >> 32); a.worker = worker; a.index_offset = index_offset;
     a.norms_out = norms_out; a.code_out = code_out; a.sign_out = sign_out;
     const bool fast = aligned(x, 16) && (index_offset & 3) == 0 && aligned(code_out, fmt == kFmtByte ? 8 : 4) &&
@@ -149,11 +150,27 @@ nc_status nc_dither_encode(const float* x, uint64_t d, const uint64_t* seg_offse
     return from_hip(launch_dither_segment_encode(a, fast, (hipStream_t)stream));
 }
 
-static nc_status dither_aggregate(const float* norms, size_t norm_stride, const uint8_t* code, size_t code_stride,
+nc_status nc_dither_encode(const float* x, uint64_t d, const uint64_t* seg_offsets, uint32_t num_segments,
+                           uint32_t bucket, float p, uint32_t s, uint64_t seed, uint32_t worker,
+                           uint64_t index_offset, float* norms_out, uint8_t* code_out, uint8_t* sign_out,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+    return dither_encode(0, x, d, seg_offsets, num_segments, bucket, p, s, seed, worker, index_offset, norms_out,
+                         code_out, sign_out, workspace, workspace_bytes, stream);
+}
+
+nc_status nc_dither_sta_encode(const float* x, uint64_t d, const uint64_t* seg_offsets, uint32_t num_segments,
+                               uint32_t bucket, float p, uint32_t s, uint64_t seed, uint32_t worker,
+                               uint64_t index_offset, float* norms_out, uint8_t* code_out, uint8_t* sign_out,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+    return dither_encode(1, x, d, seg_offsets, num_segments, bucket, p, s, seed, worker, index_offset, norms_out,
+                         code_out, sign_out, workspace, workspace_bytes, stream);
+}
+
+static nc_status dither_aggregate(uint32_t standard, const float* norms, size_t norm_stride, const uint8_t* code, size_t code_stride,
                                   const uint8_t* sign, size_t sign_stride, uint32_t n, uint64_t d,
                                   const uint64_t* seg_offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
                                   float* out, void* stream) {
-    if (!valid_s(s) || d > kMaxD || n == 0) return NC_ERR_INVALID;
+    if (!(standard ? valid_s_size(s) : valid_s(s)) || d > kMaxD || n == 0) return NC_ERR_INVALID;
     if (d == 0) return NC_OK;
     if (!norms || !code || !out) return NC_ERR_NULL;
     const int fmt = format_of(s);
@@ -167,7 +184,7 @@ static nc_status dither_aggregate(const float* norms, size_t norm_stride, const 
             return NC_ERR_INVALID;
     }
     a.norms = norms; a.norm_stride = norm_stride; a.code = code; a.code_stride = code_stride;
-    a.sign = sign; a.sign_stride = sign_stride; a.n = n; a.s = s; a.fmt = fmt; a.out = out;
+    a.sign = sign; a.sign_stride = sign_stride; a.n = n; a.s = s; a.fmt = fmt; a.standard = standard; a.out = out;
     const bool fast = aligned(code, 4) && aligned(out, 16) && (n == 1 || (code_stride & 3) == 0);
     return from_hip(launch_dither_aggregate(a, fast, (hipStream_t)stream));
 }
@@ -175,7 +192,13 @@ static nc_status dither_aggregate(const float* norms, size_t norm_stride, const 
 nc_status nc_dither_decode(const float* norms, const uint8_t* code, const uint8_t* sign, uint64_t d,
                            const uint64_t* seg_offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
                            float* out, void* stream) {
-    return dither_aggregate(norms, 0, code, 0, sign, 0, 1, d, seg_offsets, num_segments, bucket, s, out, stream);
+    return dither_aggregate(0, norms, 0, code, 0, sign, 0, 1, d, seg_offsets, num_segments, bucket, s, out, stream);
+}
+
+nc_status nc_dither_sta_decode(const float* norms, const uint8_t* code, const uint8_t* sign, uint64_t d,
+                               const uint64_t* seg_offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
+                               float* out, void* stream) {
+    return dither_aggregate(1, norms, 0, code, 0, sign, 0, 1, d, seg_offsets, num_segments, bucket, s, out, stream);
 }
 
 nc_status nc_sparse_nat_encode_batch(const float* x, size_t x_stride, uint32_t n, uint64_t d, uint64_t k, float scale,
@@ -238,7 +261,7 @@ nc_status nc_master_nat(const nc_agg_desc* desc, uint64_t seed, uint32_t master,
 nc_status nc_aggregate_sum(const nc_agg_desc* desc, float* out, void* stream) {
     if (!desc) return NC_ERR_NULL;
     if (desc->n == 0 || desc->d > kMaxD) return NC_ERR_INVALID;
-    if (desc->kind != NC_KIND_NAT && desc->kind != NC_KIND_DITHER) return NC_ERR_INVALID;
+    if (desc->kind != NC_KIND_NAT && desc->kind != NC_KIND_DITHER && desc->kind != NC_KIND_DITHER_STA) return NC_ERR_INVALID;
     if (desc->d == 0) return NC_OK;
     if (!out || !desc->code) return NC_ERR_NULL;
     if (desc->kind == NC_KIND_NAT) {
@@ -249,7 +272,7 @@ nc_status nc_aggregate_sum(const nc_agg_desc* desc, float* out, void* stream) {
         const bool fast = aligned(desc->code, 8) && aligned(out, 16) && (desc->n == 1 || (desc->code_stride & 7) == 0);
         return from_hip(launch_nat_aggregate(a, fast, (hipStream_t)stream));
     }
-    return dither_aggregate(desc->norms, desc->norm_stride, desc->code, desc->code_stride, desc->sign,
+    return dither_aggregate(desc->kind == NC_KIND_DITHER_STA ? 1u : 0u, desc->norms, desc->norm_stride, desc->code, desc->code_stride, desc->sign,
                             desc->sign_stride, desc->n, desc->d, desc->seg_offsets, desc->num_segments, desc->bucket,
                             desc->s, out, stream);
 }

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libnatcomp.so")
 
 NC_KIND_NAT = 0
 NC_KIND_DITHER = 1
+NC_KIND_DITHER_STA = 2
 
 _vp, _u32, _u64, _sz = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_size_t
 
@@ -64,6 +65,10 @@ def lib():
         L.nc_dither_encode.argtypes = [_vp, _u64, _vp, _u32, _u32, ctypes.c_float, _u32, _u64, _u32, _u64,
                                        _vp, _vp, _vp, _vp, _sz, _vp]
         L.nc_dither_decode.argtypes = [_vp, _vp, _vp, _u64, _vp, _u32, _u32, _u32, _vp, _vp]
+        L.nc_dither_sta_encode.argtypes = L.nc_dither_encode.argtypes
+        L.nc_dither_sta_decode.argtypes = L.nc_dither_decode.argtypes
+        L.nc_dither_sta_encode.restype = ctypes.c_int
+        L.nc_dither_sta_decode.restype = ctypes.c_int
         L.nc_aggregate_sum.argtypes = [ctypes.POINTER(AggDesc), _vp, _vp]
         L.nc_sparse_nat_encode.argtypes = [_vp, _u64, _u64, ctypes.c_float, _u64, _u32, _vp, _vp, _vp, _vp]
         L.nc_sparse_nat_encode_batch.argtypes = [_vp, _sz, _u32, _u64, _u64, ctypes.c_float, _u64, _u32, _vp, _sz,
@@ -192,8 +197,8 @@ def _segments(d, seg_offsets, bucket):
 
 
 def dither_encode(x, p, s, seed, worker=0, index_offset=0, seg_offsets=None, bucket=0,
-                  norms_out=None, code_out=None, sign_out=None, workspace=None):
-    """nc_dither_encode: returns (norms, code plane, sign plane or None)."""
+                  norms_out=None, code_out=None, sign_out=None, workspace=None, standard=False):
+    """nc_dither_encode (standard=True: nc_dither_sta_encode): returns (norms, code plane, sign plane or None)."""
     x = _dev(x, torch.float32, "x")
     d = x.numel()
     off, nseg, bucket, count = _segments(d, seg_offsets, bucket)
@@ -212,14 +217,15 @@ def dither_encode(x, p, s, seed, worker=0, index_offset=0, seg_offsets=None, buc
     _dev(sign_out, torch.uint8, "sign_out")
     _dev(workspace, torch.uint8, "workspace")
     assert norms_out.numel() >= count
-    _check(lib().nc_dither_encode(_ptr(x), d, _ptr(off), nseg, bucket, float(p), s, seed, worker, index_offset,
-                                  _ptr(norms_out), _ptr(code_out), _ptr(sign_out), _ptr(workspace),
-                                  0 if workspace is None else workspace.numel(), _stream()))
+    fn = lib().nc_dither_sta_encode if standard else lib().nc_dither_encode
+    _check(fn(_ptr(x), d, _ptr(off), nseg, bucket, float(p), s, seed, worker, index_offset,
+              _ptr(norms_out), _ptr(code_out), _ptr(sign_out), _ptr(workspace),
+              0 if workspace is None else workspace.numel(), _stream()))
     return norms_out, code_out, sign_out
 
 
-def dither_decode(norms, code, sign, d, s, seg_offsets=None, bucket=0, out=None):
-    """nc_dither_decode."""
+def dither_decode(norms, code, sign, d, s, seg_offsets=None, bucket=0, out=None, standard=False):
+    """nc_dither_decode (standard=True: nc_dither_sta_decode)."""
     norms = _dev(norms, torch.float32, "norms")
     code = _dev(code, torch.uint8, "code")
     sign = _dev(sign, torch.uint8, "sign")
@@ -228,8 +234,8 @@ def dither_decode(norms, code, sign, d, s, seg_offsets=None, bucket=0, out=None)
     if out is None:
         out = torch.empty(d, dtype=torch.float32, device=code.device)
     _dev(out, torch.float32, "out")
-    _check(lib().nc_dither_decode(_ptr(norms), _ptr(code), _ptr(sign), d, _ptr(off), nseg, bucket, s, _ptr(out),
-                                  _stream()))
+    fn = lib().nc_dither_sta_decode if standard else lib().nc_dither_decode
+    _check(fn(_ptr(norms), _ptr(code), _ptr(sign), d, _ptr(off), nseg, bucket, s, _ptr(out), _stream()))
     return out
 
 
@@ -247,7 +253,7 @@ def aggregate_sum(kind, d, code, sign=None, norms=None, s=0, seg_offsets=None, b
     if sign is not None:
         assert sign.dim() == 2 and sign.shape[0] == n
         desc.sign, desc.sign_stride = sign.data_ptr(), sign.shape[1]
-    if kind == NC_KIND_DITHER:
+    if kind in (NC_KIND_DITHER, NC_KIND_DITHER_STA):
         off, nseg, bucket, count = _segments(d, seg_offsets, bucket)
         assert norms is not None and norms.dim() == 2 and norms.shape[0] == n and norms.shape[1] >= count
         desc.norms, desc.norm_stride = norms.data_ptr(), norms.shape[1]

@@ -39,7 +39,8 @@ def test_size_functions(nc):
     assert nc.dither_code_bytes(9, 7) == 5 and nc.dither_sign_bytes(9, 7) == 0
     assert nc.dither_code_bytes(9, 8) == 5 and nc.dither_sign_bytes(9, 8) == 2       # nibble + sign plane
     assert nc.dither_code_bytes(9, 15) == 5 and nc.dither_code_bytes(9, 16) == 9     # byte codes from s = 16
-    assert nc.dither_code_bytes(9, 0) == 0 and nc.dither_code_bytes(9, 128) == 0     # invalid s
+    assert nc.dither_code_bytes(9, 0) == 0 and nc.dither_code_bytes(9, 256) == 0     # s outside 1..255
+    assert nc.dither_code_bytes(9, 128) == 9 and nc.dither_sign_bytes(9, 255) == 2  # standard dithering sizes
     assert nc.plane_stride(1) == 256 and nc.plane_stride(256) == 256 and nc.plane_stride(257) == 512
     assert nc.segment_count(100, 0, 0, False) == 1
     assert nc.segment_count(100, 0, 8, False) == 13
