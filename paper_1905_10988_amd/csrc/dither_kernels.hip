@@ -754,6 +754,73 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
     }
 }
 
+// Plain decoder (n = 1) for the nibble formats, vector path: the lean special case of the
+// aggregate kernel.  The lane's 8 codes are loaded first; the first wavefront tabulates the 16
+// values a nibble can stand for in this chunk's segment; chunks that straddle segments (and the
+// ragged end) decode arithmetically.  Results leave through the LDS transpose.
+template <int FMT>
+__global__ __launch_bounds__(kBlock) void dither_decode_kernel(DitherAggregateArgs a) {
+    __shared__ float table[16];
+    __shared__ u32x4 tile[2 * kBlock];
+    __shared__ uint32_t slot;
+    const Segs& sg = a.segs;
+    const uint64_t cb = (uint64_t)blockIdx.x * kChunk;
+    const uint64_t ce = cb + kChunk < sg.d ? cb + kChunk : sg.d;
+    const uint32_t grp_local = threadIdx.x;
+    const uint32_t l0 = grp_local * 8;
+    const uint32_t len = (uint32_t)(ce - cb);
+    const uint32_t count = l0 >= len ? 0u : (len - l0 < 8 ? len - l0 : 8u);
+    const uint32_t* __restrict__ code_base = reinterpret_cast<const uint32_t*>(a.code + (cb >> 1));
+    const uint8_t* __restrict__ sign_base = a.sign + (cb >> 3);
+    uint32_t cw = 0, sb = 0;
+    if (count == 8) {
+        cw = load_stream(code_base + grp_local);
+        if (FMT == kFmtNibble) sb = load_stream(sign_base + grp_local);
+    }
+    const uint32_t s0 = seg_find_block(sg, cb, &slot);
+    const bool one_segment = seg_end(sg, s0) >= ce;
+    uint32_t bits[8];
+    if (one_segment) {
+        if (threadIdx.x < 16) {
+            const float norm = a.norms[s0];
+            table[threadIdx.x] = (FMT == kFmtFused)
+                                     ? dither_value(norm, a.s, threadIdx.x & 7u, threadIdx.x >> 3, a.standard)
+                                     : dither_value(norm, a.s, threadIdx.x, 0u, a.standard);
+        }
+        __syncthreads();
+        asm volatile("" : "+v"(cw), "+v"(sb));  // no table addresses computed ahead of the barrier
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint32_t v = f32_bits(table[(cw >> (4 * j)) & 15u]);
+            if (FMT == kFmtNibble) v |= (sb << (31 - j)) & 0x80000000u;
+            bits[j] = v;
+        }
+    } else if (count == 8) {
+        const uint32_t last = seg_count(sg) - 1;
+        uint32_t s = seg_find(sg, cb + l0);
+        uint64_t se = seg_end(sg, s);
+        float norm = a.norms[s];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            while (cb + l0 + j >= se && s < last) { ++s; se = seg_end(sg, s); norm = a.norms[s]; }
+            const uint32_t nib = (cw >> (4 * j)) & 15u;
+            const uint32_t c = (FMT == kFmtFused) ? (nib & 7u) : nib;
+            const uint32_t sgn = (FMT == kFmtFused) ? (nib >> 3) : ((sb >> j) & 1u);
+            bits[j] = f32_bits(dither_value(norm, a.s, c, sgn, a.standard));
+        }
+    }
+    store_tile_transposed(tile, bits, count == 8, len >> 3, a.out + cb);
+    if (count > 0 && count < 8) {  // the ragged last group of the vector
+        const uint32_t last = seg_count(sg) - 1;
+        uint32_t s = seg_find(sg, cb + l0);
+        for (uint32_t j = 0; j < count; ++j) {
+            const uint64_t i = cb + l0 + j;
+            while (i >= seg_end(sg, s) && s < last) ++s;
+            a.out[i] = dither_sum_one<FMT>(a, i, s);
+        }
+    }
+}
+
 // ------------------------------------------------------------------------ compressed norm
 // C_nat of every norm (Sec. 3: general dithering with C = C_nat sends the norm as a power of
 // two): the exponent byte and the power of two it stands for.  Norms are non-negative, so
@@ -841,6 +908,11 @@ hipError_t launch_dither_segment_encode(const DitherEncodeArgs& a, bool fast, hi
 template <bool FAST>
 static hipError_t launch_agg(const DitherAggregateArgs& a, hipStream_t st) {
     const unsigned chunks = (unsigned)((a.segs.d + kChunk - 1) / kChunk);
+    if (FAST && a.n == 1 && a.fmt != kFmtByte) {  // plain decoder
+        if (a.fmt == kFmtFused) dither_decode_kernel<kFmtFused><<<chunks, kBlock, 0, st>>>(a);
+        else dither_decode_kernel<kFmtNibble><<<chunks, kBlock, 0, st>>>(a);
+        return hipGetLastError();
+    }
     switch (a.fmt) {
         case kFmtFused: dither_aggregate_kernel<kFmtFused, FAST><<<chunks, kBlock, 0, st>>>(a); break;
         case kFmtNibble: dither_aggregate_kernel<kFmtNibble, FAST><<<chunks, kBlock, 0, st>>>(a); break;
