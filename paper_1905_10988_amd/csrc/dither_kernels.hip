@@ -32,17 +32,37 @@ __device__ __forceinline__ uint32_t seg_find(const Segs& sg, uint64_t i) {
     }
     return sg.bucket ? (uint32_t)(i / sg.bucket) : 0u;
 }
-// The same answer for a workgroup-uniform position, found by the whole workgroup: with at
-// most kBlock segments one round of loads (lane t tests segment t) replaces the dependent
-// chain of a binary search.  `slot` is one LDS word; all lanes must call.
-__device__ __forceinline__ uint32_t seg_find_block(const Segs& sg, uint64_t i, uint32_t* slot) {
-    if (!sg.offsets) return sg.bucket ? (uint32_t)(i / sg.bucket) : 0u;
-    if (sg.num_segments > (uint32_t)kBlock || blockDim.x != (unsigned)kBlock) return seg_find(sg, i);
-    if (threadIdx.x == 0) *slot = 0;
+// The segment of a workgroup-uniform position together with what the kernels need next: its
+// bounds and, if aux is given, aux[segment] (a norm or its reciprocal).  With at most kBlock
+// segments the whole workgroup searches at once: lane t loads segment t's bounds and aux value
+// in one round of loads and the lane whose segment holds i publishes them, which replaces the
+// dependent chain binary search -> bounds -> aux.  `slot` is LDS; all lanes must call.
+struct SegHit {
+    uint32_t s;
+    float aux;
+    uint64_t begin, end;
+};
+__device__ __forceinline__ SegHit seg_find_block(const Segs& sg, uint64_t i, const float* __restrict__ aux,
+                                                 SegHit* slot) {
+    SegHit h;
+    if (!sg.offsets || sg.num_segments > (uint32_t)kBlock || blockDim.x != (unsigned)kBlock) {
+        h.s = seg_find(sg, i);
+        if (sg.offsets) {
+            h.begin = sg.offsets[h.s];
+            h.end = sg.offsets[h.s + 1];
+        } else {
+            h.begin = sg.bucket ? (uint64_t)h.s * sg.bucket : 0ull;
+            h.end = sg.bucket && h.begin + sg.bucket < sg.d ? h.begin + sg.bucket : sg.d;
+        }
+        h.aux = aux ? aux[h.s] : 0.0f;
+        return h;
+    }
+    if (threadIdx.x == 0) *slot = SegHit{0u, 0.0f, 0ull, 0ull};  // offsets that do not cover i
     __syncthreads();
     if (threadIdx.x < sg.num_segments) {
         const uint64_t b = sg.offsets[threadIdx.x], e = sg.offsets[threadIdx.x + 1];
-        if (b <= i && i < e) *slot = threadIdx.x;  // at most one non-empty segment holds i
+        const float v = aux ? aux[threadIdx.x] : 0.0f;
+        if (b <= i && i < e) *slot = SegHit{threadIdx.x, v, b, e};  // at most one non-empty segment holds i
     }
     __syncthreads();
     return *slot;
@@ -60,6 +80,46 @@ __device__ __forceinline__ uint64_t seg_end(const Segs& sg, uint32_t s) {
 __device__ __forceinline__ uint32_t seg_count(const Segs& sg) {
     if (sg.offsets) return sg.num_segments;
     return sg.bucket ? (uint32_t)((sg.d + sg.bucket - 1) / sg.bucket) : 1u;
+}
+
+// Segment boundaries inside one chunk, staged in LDS.  Segment s0 holds the chunk's first
+// element cb; lane t looks at the begin of segment s0 + 1 + t and, if it lies before the
+// chunk's end ce, writes its chunk-local position to bnd[t] (ascending; empty segments repeat
+// a position).  Returns how many were staged; kBlock means "kBlock or more", and the caller
+// falls back to searching the offsets in global memory.  All lanes must call (barrier inside).
+// The segment of chunk-local position l is then s0 + #{t : bnd[t] <= l}.
+__device__ __forceinline__ uint32_t stage_boundaries(const Segs& sg, uint64_t cb, uint64_t ce, uint32_t s0,
+                                                     uint32_t* bnd) {
+    const uint32_t s = s0 + 1 + threadIdx.x;
+    bool in = false;
+    if (s < seg_count(sg)) {
+        const uint64_t b = seg_begin(sg, s);
+        if (b < ce) { bnd[threadIdx.x] = (uint32_t)(b - cb); in = true; }
+    }
+    return (uint32_t)__syncthreads_count(in);
+}
+// A lane's position in the staged boundaries: idx = number of boundaries at or before the
+// lane's current element (its segment is s0 + idx), next = position of the following one.
+struct SegCursor {
+    uint32_t idx, next;
+};
+__device__ __forceinline__ SegCursor cursor_at(const uint32_t* bnd, uint32_t nb, uint32_t l) {
+    uint32_t lo = 0, hi = nb;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (bnd[mid] <= l) lo = mid + 1; else hi = mid;
+    }
+    return SegCursor{lo, lo < nb ? bnd[lo] : 0xFFFFFFFFu};
+}
+// Moves the cursor forward to position l; true if the segment changed.
+__device__ __forceinline__ bool cursor_advance(SegCursor& c, const uint32_t* bnd, uint32_t nb, uint32_t l) {
+    bool moved = false;
+    while (l >= c.next) {
+        ++c.idx;
+        c.next = c.idx < nb ? bnd[c.idx] : 0xFFFFFFFFu;
+        moved = true;
+    }
+    return moved;
 }
 
 // ------------------------------------------------------------------------ norms
@@ -283,24 +343,24 @@ __device__ __forceinline__ void encode_group(const DitherEncodeArgs& a, const ui
 }
 
 // ------------------------------------------------------------------------ vector (quad) encode
-// Level codes of one quad with a common reciprocal norm.
-__device__ __forceinline__ void levels4(u32x4 v, float inv, const uint32_t rc[4], const LevelParams& lp,
+// Level codes of one quad; inv[j] is the reciprocal norm of element j's segment.
+__device__ __forceinline__ void levels4(u32x4 v, const float inv[4], const uint32_t rc[4], const LevelParams& lp,
                                         uint32_t c[4]) {
     if (lp.standard) {
-        c[0] = dither_level_standard(bits_f32(v.x), inv, rc[0], lp);
-        c[1] = dither_level_standard(bits_f32(v.y), inv, rc[1], lp);
-        c[2] = dither_level_standard(bits_f32(v.z), inv, rc[2], lp);
-        c[3] = dither_level_standard(bits_f32(v.w), inv, rc[3], lp);
+        c[0] = dither_level_standard(bits_f32(v.x), inv[0], rc[0], lp);
+        c[1] = dither_level_standard(bits_f32(v.y), inv[1], rc[1], lp);
+        c[2] = dither_level_standard(bits_f32(v.z), inv[2], rc[2], lp);
+        c[3] = dither_level_standard(bits_f32(v.w), inv[3], rc[3], lp);
     } else if (lp.s <= 95) {
-        c[0] = dither_level<true>(bits_f32(v.x), inv, rc[0], lp);
-        c[1] = dither_level<true>(bits_f32(v.y), inv, rc[1], lp);
-        c[2] = dither_level<true>(bits_f32(v.z), inv, rc[2], lp);
-        c[3] = dither_level<true>(bits_f32(v.w), inv, rc[3], lp);
+        c[0] = dither_level<true>(bits_f32(v.x), inv[0], rc[0], lp);
+        c[1] = dither_level<true>(bits_f32(v.y), inv[1], rc[1], lp);
+        c[2] = dither_level<true>(bits_f32(v.z), inv[2], rc[2], lp);
+        c[3] = dither_level<true>(bits_f32(v.w), inv[3], rc[3], lp);
     } else {
-        c[0] = dither_level<false>(bits_f32(v.x), inv, rc[0], lp);
-        c[1] = dither_level<false>(bits_f32(v.y), inv, rc[1], lp);
-        c[2] = dither_level<false>(bits_f32(v.z), inv, rc[2], lp);
-        c[3] = dither_level<false>(bits_f32(v.w), inv, rc[3], lp);
+        c[0] = dither_level<false>(bits_f32(v.x), inv[0], rc[0], lp);
+        c[1] = dither_level<false>(bits_f32(v.y), inv[1], rc[1], lp);
+        c[2] = dither_level<false>(bits_f32(v.z), inv[2], rc[2], lp);
+        c[3] = dither_level<false>(bits_f32(v.w), inv[3], rc[3], lp);
     }
 }
 __device__ __forceinline__ uint32_t sign_nibble4(u32x4 v) {
@@ -319,7 +379,7 @@ __device__ __forceinline__ uint32_t sign_nibble4(u32x4 v) {
 // planes, one word of 32 sign bits from every 8th lane.
 template <int FMT>
 __device__ __forceinline__ void encode_store_quad(const DitherEncodeArgs& a, const LevelParams& lp, u32x4 v,
-                                                  float inv, uint32_t* __restrict__ code_base,
+                                                  const float inv[4], uint32_t* __restrict__ code_base,
                                                   uint32_t* __restrict__ sign_base, uint32_t q, uint64_t g_quad,
                                                   bool in) {
     uint32_t rc[4], c[4];
@@ -393,6 +453,7 @@ void dither_bucket_encode_vec_kernel(DitherEncodeArgs a) {
     const float norm = norm_value(acc, a.pnorm);
     if (threadIdx.x == 0) a.norms_out[blockIdx.x] = norm;
     const float iv = inv_of_norm(norm);
+    const float iv4[4] = {iv, iv, iv, iv};
     const LevelParams lp = level_params(a.s, a.standard);
     const uint64_t q_global = (a.index_offset + begin) >> 2;
     uint32_t* __restrict__ code_base = reinterpret_cast<uint32_t*>(a.code_out + (FMT == kFmtByte ? begin : begin >> 1));
@@ -401,7 +462,7 @@ void dither_bucket_encode_vec_kernel(DitherEncodeArgs a) {
     for (int k = 0; k < QPL; ++k) {
         const uint32_t q = threadIdx.x + k * kBlock;
         if (k * kBlock < vec_quads)  // block-uniform: skip rounds no lane takes part in
-            encode_store_quad<FMT>(a, lp, v[k], iv, code_base, sign_base, q, q_global + q, q < vec_quads);
+            encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, q_global + q, q < vec_quads);
         __builtin_amdgcn_sched_barrier(0);  // one quad at a time keeps the register count low
     }
     if (tail0 < len && threadIdx.x < 4 && tail0 + threadIdx.x * 8 < len) {
@@ -437,6 +498,27 @@ __global__ __launch_bounds__(BLOCK) void dither_bucket_encode_kernel(DitherEncod
     encode_group<FMT, FAST>(a, u, inv, begin + l0, count);
 }
 
+// Adds to acc the lane's elements that fall into the chunk-local piece [lb, le); the lane
+// holds quads t, t + kBlock, ... of the chunk.  Rows of quads the piece does not reach are
+// skipped (a workgroup-uniform test).
+template <int P, int N>
+__device__ __forceinline__ void piece_accumulate(NormAcc& acc, const u32x4 (&v)[N], uint32_t lb, uint32_t le) {
+    const uint32_t span = le - lb;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const uint32_t row0 = (uint32_t)k * kBlock * 4;
+        if (row0 < le && row0 + kBlock * 4 > lb) {
+            const uint32_t l0 = row0 + threadIdx.x * 4;
+            u32x4 m;  // zeros outside the piece add nothing
+            m.x = (l0 + 0 - lb < span) ? v[k].x : 0u;
+            m.y = (l0 + 1 - lb < span) ? v[k].y : 0u;
+            m.z = (l0 + 2 - lb < span) ? v[k].z : 0u;
+            m.w = (l0 + 3 - lb < span) ? v[k].w : 0u;
+            norm_add4_p<P>(acc, m);
+        }
+    }
+}
+
 // ------------------------------------------------------------------------ two-pass path
 // Pass 1: partial norm of every (segment, chunk) intersection, chunks of kNormChunk
 // elements.  The piece of the segment that continues into a chunk from the left goes to
@@ -447,7 +529,9 @@ __global__ __launch_bounds__(BLOCK) void dither_bucket_encode_kernel(DitherEncod
 template <bool FAST>
 __global__ __launch_bounds__(kBlock) void dither_partial_kernel(DitherEncodeArgs a) {
     __shared__ NormAcc scratch[kBlock / 64];
-    __shared__ uint32_t slot;
+    __shared__ SegHit slot;
+    __shared__ uint32_t bnd[kBlock];
+    __shared__ double piece_part[kBlock * (kBlock / 64)];  // [piece][wavefront]
     constexpr int kQuads = kNormChunk / 4 / kBlock;  // quads per lane
     const Segs& sg = a.segs;
     const uint64_t cb = (uint64_t)blockIdx.x * kNormChunk;
@@ -459,44 +543,66 @@ __global__ __launch_bounds__(kBlock) void dither_partial_kernel(DitherEncodeArgs
 #pragma unroll
         for (int k = 0; k < kQuads; ++k) v[k] = load_stream(xv + k * kBlock);
     }
-    const uint32_t s0 = seg_find_block(sg, cb, &slot);
+    const SegHit hit = seg_find_block(sg, cb, nullptr, &slot);
+    const uint32_t s0 = hit.s;
     const uint32_t nseg = seg_count(sg);
     if (vec) {  // keep the loaded values opaque up to here, so that nothing is computed from
                 // them (and held in registers) ahead of the search
 #pragma unroll
         for (int k = 0; k < kQuads; ++k) asm volatile("" : "+v"(v[k]));
     }
-    if (vec && seg_end(sg, s0) >= ce) {  // the whole chunk lies in one segment
+    if (vec && hit.end >= ce) {  // the whole chunk lies in one segment
         NormAcc acc = norm_zero();
         norm_add_quads(acc, v, a.pnorm);
         acc = norm_block_reduce<kBlock>(acc, a.pnorm, scratch);
         if (threadIdx.x == 0) {
             const double r = a.pnorm == kNormInf ? (double)acc.mx : acc.sum;
-            if (seg_begin(sg, s0) >= cb) a.head_partial[s0] = r; else a.first_partial[blockIdx.x] = r;
+            if (hit.begin >= cb) a.head_partial[s0] = r; else a.first_partial[blockIdx.x] = r;
         }
         return;
+    }
+    if (vec) {  // pieces from the staged boundaries: no global loads and one barrier for all pieces
+        const uint32_t nb = stage_boundaries(sg, cb, ce, s0, bnd);
+        if (nb < (uint32_t)kBlock) {
+            constexpr int kWaves = kBlock / 64;
+            for (uint32_t p = 0; p <= nb; ++p) {
+                const uint32_t lb = p ? bnd[p - 1] : 0u, le = p < nb ? bnd[p] : (uint32_t)kNormChunk;
+                if (le == lb) continue;  // empty segment
+#pragma unroll
+                for (int k = 0; k < kQuads; ++k) asm volatile("" : "+v"(v[k]));  // nothing hoisted out of the loop
+                NormAcc acc = norm_zero();
+                if (a.pnorm == kNormInf) piece_accumulate<kNormInf>(acc, v, lb, le);
+                else if (a.pnorm == kNormL1) piece_accumulate<kNormL1>(acc, v, lb, le);
+                else piece_accumulate<kNormL2>(acc, v, lb, le);
+                acc = norm_wave_reduce(acc, a.pnorm);
+                if ((threadIdx.x & 63) == 0)
+                    piece_part[p * kWaves + (threadIdx.x >> 6)] = a.pnorm == kNormInf ? (double)acc.mx : acc.sum;
+            }
+            __syncthreads();
+            const uint32_t p = threadIdx.x;  // nb < kBlock: one piece per lane
+            if (p <= nb) {
+                const uint32_t lb = p ? bnd[p - 1] : 0u, le = p < nb ? bnd[p] : (uint32_t)kNormChunk;
+                if (le != lb) {
+                    double r = piece_part[p * kWaves];
+#pragma unroll
+                    for (int w = 1; w < kWaves; ++w) {
+                        const double o = piece_part[p * kWaves + w];
+                        r = a.pnorm == kNormInf ? fmax(r, o) : r + o;
+                    }
+                    if (p == 0 && hit.begin < cb) a.first_partial[blockIdx.x] = r;
+                    else a.head_partial[s0 + p] = r;
+                }
+            }
+            return;
+        }
     }
     for (uint32_t s = s0; s < nseg; ++s) {  // block-uniform loop over the segments that touch the chunk
         const uint64_t sb = seg_begin(sg, s), se = seg_end(sg, s);
         if (sb >= ce) break;
         const uint64_t b = sb > cb ? sb : cb, e = se < ce ? se : ce;
         if (e <= b) continue;  // empty segment
-        NormAcc acc = norm_zero();
-        if (vec) {
-            const uint32_t lb = (uint32_t)(b - cb), span = (uint32_t)(e - b);  // chunk-local piece
-            u32x4 m[kQuads];  // the lane's values inside the piece, zeros elsewhere (zeros add nothing)
-#pragma unroll
-            for (int k = 0; k < kQuads; ++k) {
-                const uint32_t l0 = (threadIdx.x + k * kBlock) * 4;
-                m[k].x = (l0 + 0 - lb < span) ? v[k].x : 0u;
-                m[k].y = (l0 + 1 - lb < span) ? v[k].y : 0u;
-                m[k].z = (l0 + 2 - lb < span) ? v[k].z : 0u;
-                m[k].w = (l0 + 3 - lb < span) ? v[k].w : 0u;
-            }
-            norm_add_quads(acc, m, a.pnorm);
-        } else {
-            for (uint64_t i = b + threadIdx.x; i < e; i += kBlock) norm_add(acc, a.x[i], a.pnorm);
-        }
+        NormAcc acc = norm_zero();  // (a vector chunk with too many boundaries to stage reads x again)
+        for (uint64_t i = b + threadIdx.x; i < e; i += kBlock) norm_add(acc, a.x[i], a.pnorm);
         acc = norm_block_reduce<kBlock>(acc, a.pnorm, scratch);
         if (threadIdx.x == 0) {
             const double r = a.pnorm == kNormInf ? (double)acc.mx : acc.sum;
@@ -527,10 +633,15 @@ __global__ __launch_bounds__(kBlock) void dither_finalize_kernel(DitherEncodeArg
         }
     }
     acc = norm_block_reduce<kBlock>(acc, a.pnorm, scratch);
+    const float norm = norm_value(acc, a.pnorm);  // the same bits in every lane
+    const float inv = inv_of_norm(norm);
     if (threadIdx.x == 0) {
-        const float norm = norm_value(acc, a.pnorm);
         a.norms_out[s] = norm;
-        a.inv_norm[s] = inv_of_norm(norm);
+        a.inv_norm[s] = inv;
+    }
+    if (a.chunk_segment && e > b) {  // the encode chunks whose first element lies in this segment
+        const uint64_t c0 = (b + kChunk - 1) / kChunk, c1 = (e - 1) / kChunk;
+        for (uint64_t c = c0 + threadIdx.x; c <= c1; c += kBlock) a.chunk_segment[c] = ChunkSegment{e, s, inv};
     }
 }
 
@@ -539,7 +650,8 @@ __global__ __launch_bounds__(kBlock) void dither_finalize_kernel(DitherEncodeArg
 // boundaries, and the ragged end of the vector, go lane-by-lane in groups of 8.
 template <int FMT, bool FAST>
 __global__ __launch_bounds__(kBlock) void dither_segment_encode_kernel(DitherEncodeArgs a) {
-    __shared__ uint32_t slot;
+    __shared__ SegHit slot;
+    __shared__ uint32_t bnd[kBlock];
     const Segs& sg = a.segs;
     const uint64_t cb = (uint64_t)blockIdx.x * kChunk;
     const uint64_t ce = cb + kChunk < sg.d ? cb + kChunk : sg.d;
@@ -555,23 +667,53 @@ __global__ __launch_bounds__(kBlock) void dither_segment_encode_kernel(DitherEnc
             if (q < vec_quads) v[k] = load_stream(xv + q);
         }
     }
-    const uint32_t s0 = seg_find_block(sg, cb, &slot);
-    const bool one_segment = seg_end(sg, s0) >= ce;  // block-uniform
+    SegHit hit;
+    if (a.chunk_segment) {  // segment offsets: the norm pass left one record per chunk
+        const ChunkSegment rec = a.chunk_segment[blockIdx.x];
+        hit = SegHit{rec.segment, rec.inv_norm, 0ull, rec.end};
+    } else {
+        hit = seg_find_block(sg, cb, a.inv_norm, &slot);  // arithmetic on the bucket size
+    }
+    const uint32_t s0 = hit.s;
+    const bool one_segment = hit.end >= ce;  // block-uniform
     uint32_t scalar_from = 0;                         // chunk-local element where the scalar part starts
-    if (FAST && one_segment) {
-        const float iv = a.inv_norm[s0];
-        const LevelParams lp = level_params(a.s, a.standard);
-        const uint64_t q_global = (a.index_offset + cb) >> 2;
-        uint32_t* __restrict__ code_base = reinterpret_cast<uint32_t*>(a.code_out + (FMT == kFmtByte ? cb : cb >> 1));
-        uint32_t* __restrict__ sign_base = reinterpret_cast<uint32_t*>(a.sign_out + (cb >> 3));
+    uint32_t nb = one_segment ? 0u : (uint32_t)kBlock;  // staged boundaries (kBlock: not staged)
+    if (FAST) {
+        if (!one_segment) nb = stage_boundaries(sg, cb, ce, s0, bnd);
+        if (nb < (uint32_t)kBlock) {
+            const LevelParams lp = level_params(a.s, a.standard);
+            const uint64_t q_global = (a.index_offset + cb) >> 2;
+            uint32_t* __restrict__ code_base =
+                reinterpret_cast<uint32_t*>(a.code_out + (FMT == kFmtByte ? cb : cb >> 1));
+            uint32_t* __restrict__ sign_base = reinterpret_cast<uint32_t*>(a.sign_out + (cb >> 3));
+            if (one_segment) {
+                const float iv = hit.aux;
+                const float iv4[4] = {iv, iv, iv, iv};
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            const uint32_t q = threadIdx.x + k * kBlock;
-            if (k * kBlock < vec_quads)
-                encode_store_quad<FMT>(a, lp, v[k], iv, code_base, sign_base, q, q_global + q, q < vec_quads);
+                for (int k = 0; k < 2; ++k) {
+                    const uint32_t q = threadIdx.x + k * kBlock;
+                    if (k * kBlock < vec_quads)
+                        encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, q_global + q, q < vec_quads);
+                }
+            } else {  // each element takes the reciprocal norm of its own segment
+                for (int k = 0; k < 2; ++k) {
+                    const uint32_t q = threadIdx.x + k * kBlock;
+                    if (k * kBlock < vec_quads) {
+                        SegCursor cur = cursor_at(bnd, nb, q * 4);
+                        float iv = a.inv_norm[s0 + cur.idx];
+                        float iv4[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            if (cursor_advance(cur, bnd, nb, q * 4 + j)) iv = a.inv_norm[s0 + cur.idx];
+                            iv4[j] = iv;
+                        }
+                        encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, q_global + q, q < vec_quads);
+                    }
+                }
+            }
+            scalar_from = vec_quads * 4;
+            if (scalar_from >= len) return;
         }
-        scalar_from = vec_quads * 4;
-        if (scalar_from >= len) return;
     }
     const uint64_t i0 = cb + scalar_from + (uint64_t)threadIdx.x * 8;
     if (i0 >= ce) return;
@@ -580,7 +722,7 @@ __global__ __launch_bounds__(kBlock) void dither_segment_encode_kernel(DitherEnc
     load8<false>(a.x, i0, count, u);
     float inv[8];
     if (one_segment) {
-        const float iv = a.inv_norm[s0];
+        const float iv = hit.aux;
 #pragma unroll
         for (int j = 0; j < 8; ++j) inv[j] = iv;
     } else {
@@ -673,7 +815,8 @@ template <int FMT, bool VEC>
 __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregateArgs a) {
     __shared__ float table[16 * 16];
     __shared__ u32x4 tile[2 * kBlock];
-    __shared__ uint32_t slot;
+    __shared__ SegHit slot;
+    __shared__ uint32_t bnd[kBlock];
     const Segs& sg = a.segs;
     const uint64_t cb = (uint64_t)blockIdx.x * kChunk;
     const uint64_t ce = cb + kChunk < sg.d ? cb + kChunk : sg.d;
@@ -689,8 +832,9 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
         if (n_first == 8) dither_load_codes<FMT, 8>(a, grp, 0, cw0, sb0);
         else if (n_first == 1) dither_load_codes<FMT, 1>(a, grp, 0, cw0, sb0);
     }
-    const uint32_t s0 = seg_find_block(sg, cb, &slot);
-    const bool one_segment = seg_end(sg, s0) >= ce;
+    const SegHit hit = seg_find_block(sg, cb, nullptr, &slot);
+    const uint32_t s0 = hit.s;
+    const bool one_segment = hit.end >= ce;
     float acc[8] = {-0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f};
 
     if (kTables && one_segment) {
@@ -726,15 +870,28 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
 #pragma unroll
             for (int j = 0; j < 8; ++j) if ((uint32_t)j < count) acc[j] = dither_sum_one<FMT>(a, i0 + j, s0);
         }
-    } else if (count) {
-        const uint32_t last = seg_count(sg) - 1;
-        uint32_t s = one_segment ? s0 : seg_find(sg, i0);
-        uint64_t se = seg_end(sg, s);
+    } else {
+        const uint32_t nb = one_segment ? 0u : stage_boundaries(sg, cb, ce, s0, bnd);  // block-uniform
+        if (count && nb < (uint32_t)kBlock) {
+            const uint32_t l0 = threadIdx.x * 8;
+            SegCursor cur = cursor_at(bnd, nb, l0);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            if ((uint32_t)j < count) {
-                while (i0 + j >= se && s < last) { ++s; se = seg_end(sg, s); }
-                acc[j] = dither_sum_one<FMT>(a, i0 + j, s);
+            for (int j = 0; j < 8; ++j) {
+                if ((uint32_t)j < count) {
+                    cursor_advance(cur, bnd, nb, l0 + j);
+                    acc[j] = dither_sum_one<FMT>(a, i0 + j, s0 + cur.idx);
+                }
+            }
+        } else if (count) {  // too many boundaries to stage: search the offsets
+            const uint32_t last = seg_count(sg) - 1;
+            uint32_t s = seg_find(sg, i0);
+            uint64_t se = seg_end(sg, s);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if ((uint32_t)j < count) {
+                    while (i0 + j >= se && s < last) { ++s; se = seg_end(sg, s); }
+                    acc[j] = dither_sum_one<FMT>(a, i0 + j, s);
+                }
             }
         }
     }
@@ -762,7 +919,8 @@ template <int FMT>
 __global__ __launch_bounds__(kBlock) void dither_decode_kernel(DitherAggregateArgs a) {
     __shared__ float table[16];
     __shared__ u32x4 tile[2 * kBlock];
-    __shared__ uint32_t slot;
+    __shared__ SegHit slot;
+    __shared__ uint32_t bnd[kBlock];
     const Segs& sg = a.segs;
     const uint64_t cb = (uint64_t)blockIdx.x * kChunk;
     const uint64_t ce = cb + kChunk < sg.d ? cb + kChunk : sg.d;
@@ -777,12 +935,13 @@ __global__ __launch_bounds__(kBlock) void dither_decode_kernel(DitherAggregateAr
         cw = load_stream(code_base + grp_local);
         if (FMT == kFmtNibble) sb = load_stream(sign_base + grp_local);
     }
-    const uint32_t s0 = seg_find_block(sg, cb, &slot);
-    const bool one_segment = seg_end(sg, s0) >= ce;
+    const SegHit hit = seg_find_block(sg, cb, a.norms, &slot);
+    const uint32_t s0 = hit.s;
+    const bool one_segment = hit.end >= ce;
     uint32_t bits[8];
     if (one_segment) {
         if (threadIdx.x < 16) {
-            const float norm = a.norms[s0];
+            const float norm = hit.aux;
             table[threadIdx.x] = (FMT == kFmtFused)
                                      ? dither_value(norm, a.s, threadIdx.x & 7u, threadIdx.x >> 3, a.standard)
                                      : dither_value(norm, a.s, threadIdx.x, 0u, a.standard);
@@ -795,14 +954,23 @@ __global__ __launch_bounds__(kBlock) void dither_decode_kernel(DitherAggregateAr
             if (FMT == kFmtNibble) v |= (sb << (31 - j)) & 0x80000000u;
             bits[j] = v;
         }
-    } else if (count == 8) {
-        const uint32_t last = seg_count(sg) - 1;
-        uint32_t s = seg_find(sg, cb + l0);
-        uint64_t se = seg_end(sg, s);
-        float norm = a.norms[s];
+    } else {
+        const uint32_t nb = stage_boundaries(sg, cb, ce, s0, bnd);  // block-uniform branch
+        SegCursor cur;
+        if (nb < (uint32_t)kBlock) cur = cursor_at(bnd, nb, l0);
+        else cur = SegCursor{count ? seg_find(sg, cb + l0) - s0 : 0u, 0u};
+        float norm = a.norms[s0 + cur.idx];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            while (cb + l0 + j >= se && s < last) { ++s; se = seg_end(sg, s); norm = a.norms[s]; }
+            if (nb < (uint32_t)kBlock) {
+                if (cursor_advance(cur, bnd, nb, l0 + j)) norm = a.norms[s0 + cur.idx];
+            } else if (count) {
+                const uint32_t last = seg_count(sg) - 1;
+                while (cb + l0 + j >= seg_end(sg, s0 + cur.idx) && s0 + cur.idx < last) {
+                    ++cur.idx;
+                    norm = a.norms[s0 + cur.idx];
+                }
+            }
             const uint32_t nib = (cw >> (4 * j)) & 15u;
             const uint32_t c = (FMT == kFmtFused) ? (nib & 7u) : nib;
             const uint32_t sgn = (FMT == kFmtFused) ? (nib >> 3) : ((sb >> j) & 1u);

@@ -39,6 +39,13 @@ constexpr uint32_t kChunk = 2048;          // elements per workgroup in the chun
 constexpr uint32_t kNormChunk = 8192;      // elements per workgroup in the partial-norm pass (256 lanes x 8 quads)
 constexpr uint32_t kMaxOnePassBucket = 8192;  // largest bucket one workgroup keeps in registers
 
+// What the encode pass needs to know about the segment that holds a chunk's first element
+// (segment-offset mode: written by the norm-finishing pass, one record per kChunk elements).
+struct ChunkSegment {
+    uint64_t end;      // one past the segment's last element
+    uint32_t segment;  // its index
+    float inv_norm;    // reciprocal of its norm (0 for a norm below the smallest normal number)
+};
 struct DitherEncodeArgs {
     const float* x; Segs segs;
     int pnorm; uint32_t s; int fmt; uint32_t standard;   // standard = 1: levels j/s instead of 2^(j-s)
@@ -47,6 +54,7 @@ struct DitherEncodeArgs {
     double* first_partial;   // one per norm chunk (two-pass path only)
     double* head_partial;    // one per segment    (two-pass path only)
     float* inv_norm;         // one per segment    (two-pass path only)
+    ChunkSegment* chunk_segment;  // one per kChunk elements (two-pass path with segment offsets only)
 };
 struct DitherAggregateArgs {
     const float* norms; size_t norm_stride; const uint8_t* code; size_t code_stride;

@@ -113,7 +113,8 @@ size_t nc_dither_workspace_bytes(uint64_t d, uint32_t num_segments, uint32_t buc
     if (!have_offsets && one_pass_bucket(nullptr, bucket)) return 0;
     const uint64_t nseg = nc_segment_count(d, num_segments, bucket, have_offsets);
     const uint64_t chunks = (d + kNormChunk - 1) / kNormChunk;
-    return (size_t)(8 * chunks + 8 * nseg + align8(4 * nseg));
+    const uint64_t code_chunks = have_offsets ? (d + kChunk - 1) / kChunk : 0;
+    return (size_t)(8 * chunks + 8 * nseg + align8(4 * nseg) + sizeof(ChunkSegment) * code_chunks);
 }
 
 static nc_status dither_encode(uint32_t standard, const float* x, uint64_t d, const uint64_t* seg_offsets,
@@ -147,6 +148,9 @@ static nc_status dither_encode(uint32_t standard, const float* x, uint64_t d, co
     a.first_partial = static_cast<double*>(workspace);
     a.head_partial = a.first_partial + chunks;
     a.inv_norm = reinterpret_cast<float*>(a.head_partial + nseg);
+    a.chunk_segment = seg_offsets ? reinterpret_cast<ChunkSegment*>(static_cast<char*>(workspace) + 8 * chunks +
+                                                                    8 * nseg + align8(4 * nseg))
+                                  : nullptr;
     return from_hip(launch_dither_segment_encode(a, fast, (hipStream_t)stream));
 }
 

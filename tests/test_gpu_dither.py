@@ -103,6 +103,34 @@ def test_layer_segments(nc, oracle, wl):
     roundtrip(nc, oracle, x, 2, 8, offsets=np.array([0, d], np.uint64))
 
 
+@pytest.mark.parametrize("max_len", [9, 40, 700])
+def test_many_small_segments(nc, oracle, wl, max_len):
+    """Segments of 0..max_len elements: hundreds of boundaries in one chunk (more than the
+    kernels stage in LDS when max_len is 9), a few per chunk when max_len is 700; encode,
+    decode and a 3-worker sum."""
+    d, n, s = 45_011, 3, 8
+    rng = np.random.default_rng(100 + max_len)
+    lens = rng.integers(0, max_len + 1, size=2 * d // max(max_len, 1) + 64)
+    ends = np.minimum(np.cumsum(lens), d)
+    off = np.concatenate([[0], ends[ends < d], [d]]).astype(np.uint64)
+    x = wl.layered_laplace(1, off, seed=51)
+    for p, sl in [(2, 8), (INF, 4), (1, 20)]:
+        roundtrip(nc, oracle, x, p, sl, offsets=off)
+    offdev, nseg = dev(off), off.size - 1
+    cs, ss = nc.dither_code_bytes(d, s), nc.dither_sign_bytes(d, s)
+    norms = torch.zeros((n, nseg), dtype=torch.float32, device="cuda")
+    code = torch.zeros((n, cs), dtype=torch.uint8, device="cuda")
+    sign = torch.zeros((n, ss), dtype=torch.uint8, device="cuda")
+    for w in range(n):
+        xw = wl.layered_laplace(w, off, seed=52)
+        nc.dither_encode(dev(xw), 2, s, 23, worker=w, seg_offsets=offdev, norms_out=norms[w],
+                         code_out=code[w], sign_out=sign[w])
+    got = host(nc.aggregate_sum(nc.NC_KIND_DITHER, d, code, sign, norms, s=s, seg_offsets=offdev))
+    o64, o32, oa = oracle.aggregate_dither(host(norms), host(code), host(sign), d, s, offsets=off)
+    assert np.array_equal(got.view(np.uint32), o32.view(np.uint32))
+    assert np.all(np.abs(got.astype(np.float64) - o64) <= 1e-5 * oa)
+
+
 @pytest.mark.parametrize("d", [1, 2, 7, 8, 9, 15, 17, 2047, 2049, 4097])
 def test_ragged_sizes(nc, oracle, wl, d):
     x = wl.bucketed_gaussian(0, d=d, bucket=64, seed=d)
