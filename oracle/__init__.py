@@ -17,6 +17,7 @@ _lib = None
 _u8p = ctypes.POINTER(ctypes.c_uint8)
 _u32p = ctypes.POINTER(ctypes.c_uint32)
 _u64p = ctypes.POINTER(ctypes.c_uint64)
+_i64p = ctypes.POINTER(ctypes.c_int64)
 _f32p = ctypes.POINTER(ctypes.c_float)
 _f64p = ctypes.POINTER(ctypes.c_double)
 _u32, _u64, _f64 = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_double
@@ -31,6 +32,12 @@ def lib():
     if _lib is None:
         path = _build.build(force=False)
         L = ctypes.CDLL(path)
+        L.orc_clip_encode.argtypes = [_f32p, _u64, _u64, _u32, _u64, _u8p]
+        L.orc_clip_encode.restype = None
+        L.orc_clip_decode.argtypes = [_u8p, _u64, _f32p]
+        L.orc_clip_decode.restype = None
+        L.orc_clip_aggregate.argtypes = [_u8p, _u64, _u32, _u64, _u64, _u32, _u64, _i64p, _u8p, _u8p]
+        L.orc_clip_aggregate.restype = None
         L.orc_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
         L.orc_philox4x32_10.restype = None
         L.orc_random_word.argtypes = [_u64, _u32, _u32, _u64]
@@ -384,3 +391,32 @@ def sta_decode(norms, code, sign, d, s, offsets=None, bucket=0):
     lib().orc_sta_decode(_ptr(norms, _f32p), _ptr(code, _u8p), _ptr(sign, _u8p), d, _ptr(off, _u64p), nseg, bucket,
                          s, _ptr(out, _f32p))
     return out
+
+
+# ------------------------------------------------------------------ clipped 8-bit format, integer aggregation
+def clip_encode(x, seed, worker=0, index_offset=0):
+    """One byte per element: sign << 7 | zero flag << 6 | clip(exponent of C_nat(x), -50, 10) + 50."""
+    x = _c(x, np.float32)
+    out = np.zeros(x.size, np.uint8)
+    lib().orc_clip_encode(_ptr(x, _f32p), x.size, seed, worker, index_offset, _ptr(out, _u8p))
+    return out
+
+
+def clip_decode(code):
+    code = _c(code, np.uint8)
+    out = np.zeros(code.size, np.float32)
+    lib().orc_clip_decode(_ptr(code, _u8p), code.size, _ptr(out, _f32p))
+    return out
+
+
+def clip_aggregate(code, d, seed, master=0, index_offset=0):
+    """Integer sum (units of 2^-50) of the n byte streams and C_nat of it: (sums int64, exponent plane,
+    sign plane)."""
+    code = _c(code, np.uint8)
+    assert code.ndim == 2 and code.shape[1] >= d
+    total = np.zeros(d, np.int64)
+    e = np.zeros(d, np.uint8)
+    s = np.zeros((d + 7) // 8, np.uint8)
+    lib().orc_clip_aggregate(_ptr(code, _u8p), code.shape[1], code.shape[0], d, seed, master, index_offset,
+                             _ptr(total, _i64p), _ptr(e, _u8p), _ptr(s, _u8p))
+    return total, e, s

@@ -657,3 +657,98 @@ void orc_sta_decode(const float *norms, const uint8_t *code, const uint8_t *sign
         }
     }
 }
+
+/* ------------------------------------------------------------------------ */
+/* Clipped 8-bit format and integer aggregation                             */
+/* ------------------------------------------------------------------------ */
+
+/* The 8-bit representation of the in-network aggregation prototype
+ * (experimental setup, "Implementation optimization"): one sign bit, one bit
+ * that marks a zero, and 6 bits for the exponent of C_nat(x) clipped to the
+ * range -50 .. 10, so that the aggregator can hold every value as a 64-bit
+ * integer in units of 2^-50.  Byte layout chosen here: bit 7 = sign, bit 6 =
+ * zero flag, bits 5..0 = clip(exponent, -50, 10) + 50 (0 when the flag is set).
+ * Readings: "clip" clamps, so a value below 2^-50 becomes 2^-50 and a value
+ * above 2^10 (Inf and NaN included) becomes 2^10, which biases the operator
+ * outside the range exactly as the text accepts; C_nat(x) = 0 only for x = 0
+ * (and for a subnormal x that rounds down to exponent field 0).  The draws
+ * are those of orc_nat_encode (domain 0). */
+void orc_clip_encode(const float *x, uint64_t d, uint64_t seed, uint32_t worker, uint64_t index_offset,
+                     uint8_t *code_out)
+{
+#pragma omp parallel for
+    for (int64_t ii = 0; ii < (int64_t)d; ++ii) {
+        uint64_t i = (uint64_t)ii;
+        uint32_t u = f32_bits(x[i]);
+        uint32_t r = orc_random_word(seed, worker, ORC_DOMAIN_NAT, index_offset + i);
+        int32_t e = (int32_t)orc_nat_round(u, r); /* exponent field of C_nat(x) */
+        uint32_t byte;
+        if (e == 0) {
+            byte = 0x40u;
+        } else {
+            int32_t expo = e - 127;
+            if (expo < -50) expo = -50;
+            if (expo > 10) expo = 10;
+            byte = (uint32_t)(expo + 50);
+        }
+        code_out[i] = (uint8_t)(byte | ((u >> 31) << 7));
+    }
+}
+
+/* The value a byte stands for as an integer in units of 2^-50: 0 if the zero
+ * flag is set, else +-2^field.  Fields 61..63 are never produced by the encoder;
+ * they are taken literally (arithmetic modulo 2^64). */
+static uint64_t clip_units(uint8_t byte)
+{
+    uint64_t mag = (byte & 0x40u) ? 0ull : (1ull << (byte & 63u));
+    return (byte & 0x80u) ? (0ull - mag) : mag;
+}
+
+/* Decoded binary32 value: sign and 2^(field - 50), or a signed zero. */
+void orc_clip_decode(const uint8_t *code, uint64_t d, float *out)
+{
+    for (uint64_t i = 0; i < d; ++i) {
+        uint32_t sign = (uint32_t)(code[i] >> 7) << 31;
+        uint32_t mag = (code[i] & 0x40u) ? 0u : (((uint32_t)(code[i] & 63u) - 50u + 127u) << 23);
+        out[i] = bits_f32(sign | mag);
+    }
+}
+
+/* Aggregator of the prototype (experimental setup; appendix on fast
+ * aggregation): every value is restored as a 64-bit integer with one non-zero
+ * bit, the n workers are added as integers (exact; two's complement, so the
+ * order does not matter; n * 2^60 < 2^63 holds for n <= 7, beyond that the sum
+ * is exact modulo 2^64), and the sum is compressed again with C_nat (Algorithm
+ * 1, master side) from the master's stream (domain 3).  C_nat of an integer
+ * S != 0 with 2^k <= |S| < 2^(k+1): exponent k + 1 with probability
+ * (|S| - 2^k) / 2^k, else k.  Reading: the probability is compared in 32 bits,
+ * r < floor(((|S| - 2^k) / 2^k) * 2^32), the same rule as orc_nat_round when |S|
+ * has at most 24 significant bits; below that, at most 2^-32 of probability is
+ * lost to truncation.  Outputs: sum_out[i] (may be NULL) in units of 2^-50; the
+ * planes of orc_nat_encode for the compressed sum, exponent field k - 50 + 127
+ * (+1), 0 for S = 0; sign bit set for S < 0. */
+void orc_clip_aggregate(const uint8_t *code, uint64_t code_stride, uint32_t n, uint64_t d, uint64_t seed,
+                        uint32_t master, uint64_t index_offset, int64_t *sum_out, uint8_t *exp_out,
+                        uint8_t *sign_out)
+{
+    memset(sign_out, 0, (d + 7) / 8);
+    for (uint64_t i = 0; i < d; ++i) {
+        uint64_t total = 0;
+        for (uint32_t w = 0; w < n; ++w) total += clip_units(code[(uint64_t)w * code_stride + i]);
+        if (sum_out) sum_out[i] = (int64_t)total;
+        uint32_t negative = (uint32_t)(total >> 63);
+        uint64_t mag = negative ? (0ull - total) : total;
+        uint32_t e = 0;
+        if (mag != 0) {
+            int k = 63;
+            while (!((mag >> k) & 1ull)) --k;
+            uint64_t rest = mag - (1ull << k);  /* < 2^k */
+            /* floor(rest / 2^k * 2^32) */
+            uint64_t threshold = k >= 32 ? (rest >> (k - 32)) : (rest << (32 - k));
+            uint32_t r = orc_random_word(seed, master, ORC_DOMAIN_MASTER, index_offset + i);
+            e = (uint32_t)(k - 50 + 127) + (((uint64_t)r < threshold) ? 1u : 0u);
+        }
+        exp_out[i] = (uint8_t)e;
+        sign_out[i >> 3] |= (uint8_t)(negative << (i & 7));
+    }
+}
