@@ -196,6 +196,48 @@ nc_status nc_master_nat(const nc_agg_desc *desc, uint64_t seed, uint32_t master,
                         uint8_t *exp_out, uint8_t *sign_out, void *stream);
 
 /* ----------------------------------------------------------------------------------------
+ * The 8-bit representation and the integer aggregator of the in-network aggregation
+ * prototype (experimental setup, paragraph "Implementation optimization"; appendix "Natural
+ * Compression and Dithering Allow for Fast Aggregation").
+ *
+ * One byte per element: bit 7 = sign of x, bit 6 = 1 marks C_nat(x) = 0, bits 5..0 = field =
+ * clip(exponent of C_nat(x), -50, 10) + 50 (0 when bit 6 is set).  The clip clamps: magnitudes
+ * below 2^-50 become 2^-50, above 2^10 (Inf, NaN) become 2^10.  The random words are those of
+ * nc_nat_encode (same seed, worker, index_offset: the byte is the clipped form of that call's
+ * exponent and sign).
+ *
+ * nc_nat_clip_encode: n workers' vectors in one launch.
+ *   x            DEVICE, worker w at x + w * x_stride (floats), d elements each.
+ *   code_out     DEVICE, worker w at code_out + w * code_stride (bytes), d bytes each.
+ *   first_worker worker id of w = 0 (ids are consecutive); strides are ignored for n = 1.
+ *   Vector path: x 16-byte and code_out 4-byte aligned, strides multiples of 4, index_offset a
+ *   multiple of 4; anything else takes a slower kernel with the same result.
+ * nc_nat_clip_decode: out[i] = +-2^(field - 50) or a signed zero (DEVICE, d floats).
+ * nc_clip_aggregate_int: every byte is restored as the 64-bit integer +-2^field (units of
+ *   2^-50; fields 61..63, which the encoder never writes, are taken literally), the n workers
+ *   are added as integers (exact for n <= 7 and in any case modulo 2^64), and the sum S is
+ *   compressed with C_nat from the master's stream (domain 3, `master` in the worker field,
+ *   element i at index_offset + i): for 2^k <= |S| < 2^(k+1) the exponent is k + 1 iff
+ *   r < floor((|S| - 2^k) / 2^k * 2^32), else k.
+ *   code       DEVICE, worker w at code + w * code_stride.
+ *   sum_out    DEVICE, d int64 (units of 2^-50), or NULL.
+ *   exp_out    DEVICE, d bytes: binary32 exponent field of the compressed sum (k - 50 + 127,
+ *              plus one when rounded up; 0 for S = 0), decodable with nc_nat_decode;
+ *   sign_out   DEVICE, nc_sign_bytes(d) bytes: bit set for S < 0.  exp_out and sign_out are
+ *              both given or both NULL; at least one of sum_out / exp_out must be given.
+ * Errors: NC_ERR_NULL for missing pointers, NC_ERR_INVALID for n = 0, strides below d, d above
+ * the library maximum or a sum_out that is not 8-byte aligned.  All calls are asynchronous on
+ * `stream`; buffers stay owned by the caller.
+ * -------------------------------------------------------------------------------------- */
+nc_status nc_nat_clip_encode(const float *x, size_t x_stride, uint32_t n, uint64_t d, uint64_t seed,
+                             uint32_t first_worker, uint64_t index_offset, uint8_t *code_out,
+                             size_t code_stride, void *stream);
+nc_status nc_nat_clip_decode(const uint8_t *code, uint64_t d, float *out, void *stream);
+nc_status nc_clip_aggregate_int(const uint8_t *code, size_t code_stride, uint32_t n, uint64_t d, uint64_t seed,
+                                uint32_t master, uint64_t index_offset, int64_t *sum_out, uint8_t *exp_out,
+                                uint8_t *sign_out, void *stream);
+
+/* ----------------------------------------------------------------------------------------
  * Random sparsification composed with natural compression, C_nat o S^k (formal definition
  * of S^q in the appendix on sparsification: S^q(x) = (d/q) xi o x with exactly q kept
  * coordinates; C_nat o S^q is in B(9d/8q - 1) by the composition theorem of Sec. 2).

@@ -96,6 +96,22 @@ struct NatMasterArgs {
 };
 hipError_t launch_nat_master(const NatAggregateArgs& a, const NatMasterArgs& m, bool fast, hipStream_t stream);
 
+// Clipped 8-bit representation (one byte per element) and the integer aggregator.
+struct ClipEncodeArgs {
+    const float* x; size_t x_stride; uint64_t d;
+    uint32_t k0, k1, first_worker; uint64_t index_offset;
+    uint8_t* code_out; size_t code_stride;
+};
+struct ClipAggregateArgs {
+    const uint8_t* code; size_t code_stride; uint32_t n; uint64_t d;
+    uint32_t k0, k1, master; uint64_t index_offset;
+    int64_t* sum_out;                       // may be null
+    uint8_t* exp_out; uint8_t* sign_out;    // both null or both set
+};
+hipError_t launch_clip_encode(const ClipEncodeArgs& a, uint32_t n, bool fast, hipStream_t stream);
+hipError_t launch_clip_decode(const uint8_t* code, uint64_t d, float* out, bool fast, hipStream_t stream);
+hipError_t launch_clip_aggregate(const ClipAggregateArgs& a, bool fast, hipStream_t stream);
+
 // `fast` promises the alignment the vector path needs (checked by the caller).
 hipError_t launch_nat_encode(const NatEncodeArgs& a, uint32_t n, bool fast, hipStream_t stream);
 hipError_t launch_nat_decode(const NatDecodeArgs& a, bool fast, hipStream_t stream);

@@ -262,6 +262,42 @@ nc_status nc_master_nat(const nc_agg_desc* desc, uint64_t seed, uint32_t master,
     return from_hip(launch_nat_master(a, m, fast, (hipStream_t)stream));
 }
 
+nc_status nc_nat_clip_encode(const float* x, size_t x_stride, uint32_t n, uint64_t d, uint64_t seed,
+                             uint32_t first_worker, uint64_t index_offset, uint8_t* code_out, size_t code_stride,
+                             void* stream) {
+    if (d > kMaxD) return NC_ERR_INVALID;
+    if (n == 0 || d == 0) return NC_OK;
+    if (!x || !code_out) return NC_ERR_NULL;
+    if (n > 1 && (x_stride < d || code_stride < d)) return NC_ERR_INVALID;
+    ClipEncodeArgs a{x, x_stride, d, (uint32_t)seed, (uint32_t)(seed >> 32), first_worker, index_offset, code_out,
+                     code_stride};
+    const bool fast = aligned(x, 16) && aligned(code_out, 4) && (index_offset & 3) == 0 &&
+                      (n == 1 || ((x_stride & 3) == 0 && (code_stride & 3) == 0));
+    return from_hip(launch_clip_encode(a, n, fast, (hipStream_t)stream));
+}
+
+nc_status nc_nat_clip_decode(const uint8_t* code, uint64_t d, float* out, void* stream) {
+    if (d > kMaxD) return NC_ERR_INVALID;
+    if (d == 0) return NC_OK;
+    if (!code || !out) return NC_ERR_NULL;
+    return from_hip(launch_clip_decode(code, d, out, aligned(code, 8) && aligned(out, 16), (hipStream_t)stream));
+}
+
+nc_status nc_clip_aggregate_int(const uint8_t* code, size_t code_stride, uint32_t n, uint64_t d, uint64_t seed,
+                                uint32_t master, uint64_t index_offset, int64_t* sum_out, uint8_t* exp_out,
+                                uint8_t* sign_out, void* stream) {
+    if (n == 0 || d > kMaxD) return NC_ERR_INVALID;
+    if (d == 0) return NC_OK;
+    if (!code || (!sum_out && !exp_out) || (exp_out == nullptr) != (sign_out == nullptr)) return NC_ERR_NULL;
+    if (n > 1 && code_stride < d) return NC_ERR_INVALID;
+    if (sum_out && !aligned(sum_out, 8)) return NC_ERR_INVALID;
+    ClipAggregateArgs a{code, code_stride, n, d, (uint32_t)seed, (uint32_t)(seed >> 32), master, index_offset,
+                        sum_out, exp_out, sign_out};
+    const bool fast = aligned(code, 8) && (n == 1 || (code_stride & 7) == 0) && (!exp_out || aligned(exp_out, 8)) &&
+                      (!sum_out || aligned(sum_out, 16)) && (index_offset & 3) == 0;
+    return from_hip(launch_clip_aggregate(a, fast, (hipStream_t)stream));
+}
+
 nc_status nc_aggregate_sum(const nc_agg_desc* desc, float* out, void* stream) {
     if (!desc) return NC_ERR_NULL;
     if (desc->n == 0 || desc->d > kMaxD) return NC_ERR_INVALID;

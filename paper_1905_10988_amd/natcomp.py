@@ -77,6 +77,12 @@ def lib():
         L.nc_norm_compress.argtypes = [_vp, _u64, _u64, _u32, _vp, _vp, _vp]
         L.nc_norm_compress.restype = ctypes.c_int
         L.nc_master_nat.argtypes = [ctypes.POINTER(AggDesc), _u64, _u32, _u64, _vp, _vp, _vp]
+        L.nc_nat_clip_encode.argtypes = [_vp, ctypes.c_size_t, _u32, _u64, _u64, _u32, _u64, _vp, ctypes.c_size_t, _vp]
+        L.nc_nat_clip_encode.restype = ctypes.c_int
+        L.nc_nat_clip_decode.argtypes = [_vp, _u64, _vp, _vp]
+        L.nc_nat_clip_decode.restype = ctypes.c_int
+        L.nc_clip_aggregate_int.argtypes = [_vp, ctypes.c_size_t, _u32, _u64, _u64, _u32, _u64, _vp, _vp, _vp, _vp]
+        L.nc_clip_aggregate_int.restype = ctypes.c_int
         L.nc_master_nat.restype = ctypes.c_int
         for name in ("nc_sparse_nat_encode", "nc_sparse_nat_encode_batch", "nc_sparse_nat_aggregate"):
             getattr(L, name).restype = ctypes.c_int
@@ -346,6 +352,65 @@ def master_nat(d, exp, sign, seed, master=0, index_offset=0, exp_out=None, sign_
     assert exp_out.numel() >= nat_exp_bytes(d) and sign_out.numel() >= sign_bytes(d)
     _check(lib().nc_master_nat(ctypes.byref(desc), seed, master, index_offset, _ptr(exp_out), _ptr(sign_out), _stream()))
     return exp_out, sign_out
+
+
+def nat_clip_encode(x, seed, first_worker=0, index_offset=0, code_out=None, d=None):
+    """nc_nat_clip_encode: x is (d,) or (n, row) float32; returns uint8 codes of shape (d,) or (n, stride)."""
+    x = _dev(x, torch.float32, "x")
+    single = x.dim() == 1
+    x2 = x.unsqueeze(0) if single else x
+    assert x2.dim() == 2
+    n, row = x2.shape
+    d = row if d is None else d
+    assert d <= row
+    if code_out is None:
+        code_out = torch.empty((n, plane_stride(d)), dtype=torch.uint8, device=x.device)
+        if single:
+            code_out = code_out[0, :d]
+    _dev(code_out, torch.uint8, "code_out")
+    c2 = code_out.unsqueeze(0) if code_out.dim() == 1 else code_out
+    assert c2.shape[0] == n and c2.shape[1] >= d
+    _check(lib().nc_nat_clip_encode(_ptr(x2), row, n, d, seed, first_worker, index_offset, _ptr(c2), c2.shape[1],
+                                    _stream()))
+    return code_out
+
+
+def nat_clip_decode(code, d, out=None):
+    """nc_nat_clip_decode."""
+    code = _dev(code, torch.uint8, "code")
+    assert code.numel() >= d
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=code.device)
+    _dev(out, torch.float32, "out")
+    assert out.numel() >= d
+    _check(lib().nc_nat_clip_decode(_ptr(code), d, _ptr(out), _stream()))
+    return out
+
+
+def clip_aggregate_int(code, d, seed, master=0, index_offset=0, want_sum=False, want_planes=True, sum_out=None,
+                       exp_out=None, sign_out=None):
+    """nc_clip_aggregate_int over the rows of a 2-D code tensor: returns (sums int64 or None, exponent plane or
+    None, sign plane or None)."""
+    code = _dev(code, torch.uint8, "code")
+    assert code.dim() == 2 and code.shape[1] >= d
+    if want_sum and sum_out is None:
+        sum_out = torch.empty(d, dtype=torch.int64, device=code.device)
+    if want_planes and exp_out is None:
+        exp_out = torch.empty(nat_exp_bytes(d), dtype=torch.uint8, device=code.device)
+    if want_planes and sign_out is None:
+        sign_out = torch.empty(sign_bytes(d), dtype=torch.uint8, device=code.device)
+    if sum_out is not None:
+        _dev(sum_out, torch.int64, "sum_out")
+        assert sum_out.numel() >= d
+    if exp_out is not None:
+        _dev(exp_out, torch.uint8, "exp_out")
+        assert exp_out.numel() >= nat_exp_bytes(d)
+    if sign_out is not None:
+        _dev(sign_out, torch.uint8, "sign_out")
+        assert sign_out.numel() >= sign_bytes(d)
+    _check(lib().nc_clip_aggregate_int(_ptr(code), code.shape[1], code.shape[0], d, seed, master, index_offset,
+                                       _ptr(sum_out), _ptr(exp_out), _ptr(sign_out), _stream()))
+    return sum_out, exp_out, sign_out
 
 
 def p_value(p):
