@@ -81,7 +81,17 @@ def secondary_kernels(nc, wl, torch, np):
     ms = _time_ms(torch, np, lambda: nc.master_nat(d, eb, sb, seed=1, exp_out=em, sign_out=sm))
     res["master_nat_n8_d25.6M"] = _entry(ms, (wl.NUM_WORKERS * 1.125 + 1.125) * d, 4.0 * d * wl.NUM_WORKERS,
                                          "fused decode+sum of 8 streams and C_nat of the sum: 9 B read + 1.125 B written per element")
-    del xb, eb, sb
+    # the 8-bit clipped representation and the int64 aggregator with master-side C_nat, same shape
+    cb = torch.empty((wl.NUM_WORKERS, nc.plane_stride(d)), dtype=torch.uint8, device="cuda")
+    ms = _time_ms(torch, np, lambda: nc.nat_clip_encode(xb, 0, code_out=cb, d=d))
+    res["clip8_encode_x8_d25.6M"] = _entry(ms, 5.0 * d * wl.NUM_WORKERS, 4.0 * d * wl.NUM_WORKERS,
+                                           "8 workers in one launch; 4 B read + 1 B written per element")
+    ms = _time_ms(torch, np, lambda: nc.clip_aggregate_int(cb, d, 1, exp_out=em, sign_out=sm))
+    res["clip8_aggregate_int64_n8_d25.6M"] = _entry(
+        ms, (wl.NUM_WORKERS + 1.125) * d, 4.0 * d * wl.NUM_WORKERS,
+        "int64 sum of 8 byte streams and C_nat of the sum: 8 B read + 1.125 B written per element "
+        "(bound by the 64-bit integer arithmetic, not by HBM)")
+    del xb, eb, sb, cb
     # config 3: D_nat^{2,8}, norm per layer tensor, encode then decode
     norms = torch.empty(nseg, dtype=torch.float32, device="cuda")
     code = torch.empty(nc.dither_code_bytes(d, 8), dtype=torch.uint8, device="cuda")

@@ -15,12 +15,20 @@ constexpr int kClipEncBlock = 128;        // lanes per encoder workgroup, 2 quad
 constexpr uint32_t kClipEncTile = 1024;   // elements per encoder workgroup
 constexpr uint32_t kClipBias = 127 - 50;  // exponent field of 2^-50: field f stands for exponent field f + 77
 
-// Byte of one element: u = bits of x, rc = complement of its random word.
-__device__ __forceinline__ uint32_t clip_byte(uint32_t u, uint32_t rc) {
-    const uint32_t e = add_sat(u << 1, rc >> 8) >> 24;  // exponent field of C_nat(x), 255 absorbing
-    const uint32_t f = min(max(e, kClipBias), kClipBias + 60u) - kClipBias;
-    return (e ? f : 0x40u) | ((u >> 24) & 0x80u);
+// Byte of one element in the top byte of the result (the low 24 bits are not meaningful):
+// u = bits of x, rc = complement of its random word.  t holds the exponent field e of
+// C_nat(x) in its top byte (255 absorbing).  The clip is two saturating operations on that
+// byte: adding 255 - 137 caps e at 137 (2^10), subtracting 255 - 137 + 77 floors it at 77
+// (2^-50) and leaves field = clip(e, 77, 137) - 77; neither touches the low 24 bits except
+// to fill or clear them on saturation.
+__device__ __forceinline__ uint32_t clip_byte_top(uint32_t u, uint32_t rc) {
+    const uint32_t t = add_sat(u << 1, rc >> 8);
+    const uint32_t capped = add_sat(t, (255u - (kClipBias + 60u)) << 24);
+    const uint32_t field = __builtin_elementwise_sub_sat(capped, (255u - 60u) << 24);
+    const uint32_t body = t < (1u << 24) ? 0x40000000u : field;  // exponent field 0: C_nat(x) = 0
+    return bitfield_insert(0x80000000u, u, body);
 }
+__device__ __forceinline__ uint32_t clip_byte(uint32_t u, uint32_t rc) { return clip_byte_top(u, rc) >> 24; }
 
 // Vector encoder: x 16-byte aligned, code_out 4-byte aligned, index_offset a multiple of 4,
 // strides keeping that for every worker.  Lane t of a workgroup takes quads t and t + 128 of
@@ -47,8 +55,8 @@ __global__ __launch_bounds__(kClipEncBlock) void clip_encode_kernel(ClipEncodeAr
         const uint64_t q = q0 + half * kClipEncBlock;
         uint32_t rc[4];
         random_words4<true>((a.index_offset >> 2) + q, worker, kDomainNat, a.k0, a.k1, rc);
-        const uint32_t bytes = clip_byte(v[half].x, rc[0]) | (clip_byte(v[half].y, rc[1]) << 8) |
-                               (clip_byte(v[half].z, rc[2]) << 16) | (clip_byte(v[half].w, rc[3]) << 24);
+        const uint32_t bytes = pack_top_bytes(clip_byte_top(v[half].x, rc[0]), clip_byte_top(v[half].y, rc[1]),
+                                              clip_byte_top(v[half].z, rc[2]), clip_byte_top(v[half].w, rc[3]));
         if (q < quads) store_stream(cv + q, bytes);
     }
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
@@ -109,6 +117,16 @@ __device__ __forceinline__ uint64_t clip_units(uint32_t byte) {
     return (byte & 0x80u) ? 0ull - mag : mag;
 }
 
+// The same for byte j of a word, with fewer operations: +1, 0 or -1 (from the sign and zero
+// bits, sign-extended to 64 bits) shifted left by the field; a two's complement shift of -1
+// gives -2^field.
+__device__ __forceinline__ uint64_t clip_units_at(uint32_t word, int j) {
+    const int32_t neg = (int32_t)(word << (24 - 8 * j)) >> 31;  // 0 or -1
+    const int32_t zer = (int32_t)(word << (25 - 8 * j)) >> 31;
+    const int64_t unit = (int64_t)((neg | 1) & ~zer);
+    return (uint64_t)unit << ((word >> (8 * j)) & 63u);
+}
+
 // C_nat of the integer sum: exponent field of the result (0 for a zero sum).  With
 // 2^k <= |S| < 2^(k+1) the exponent goes up iff r < floor((|S| - 2^k) / 2^k * 2^32): the 32
 // bits that follow the leading one.
@@ -137,7 +155,7 @@ __device__ __forceinline__ void clip_sum_chunk(const ClipAggregateArgs& a, uint6
 #pragma unroll
     for (int k = 0; k < NW; ++k) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] += clip_units(((j < 4 ? c[k].x : c[k].y) >> (8 * (j & 3))) & 255u);
+        for (int j = 0; j < 8; ++j) acc[j] += clip_units_at(j < 4 ? c[k].x : c[k].y, j & 3);
     }
 }
 
