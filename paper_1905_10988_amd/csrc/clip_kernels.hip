@@ -67,13 +67,14 @@ __global__ __launch_bounds__(kClipEncBlock) void clip_encode_kernel(ClipEncodeAr
     }
 }
 
-// Any alignment: one element per lane.
+// Any alignment: 8 consecutive elements per lane, one at a time.
 __global__ __launch_bounds__(kBlock) void clip_encode_generic_kernel(ClipEncodeArgs a) {
     const uint32_t w = blockIdx.y;
-    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (i >= a.d) return;
-    const uint32_t r = random_word(a.index_offset + i, a.first_worker + w, kDomainNat, a.k0, a.k1);
-    a.code_out[(size_t)w * a.code_stride + i] = (uint8_t)clip_byte(f32_bits(a.x[(size_t)w * a.x_stride + i]), ~r);
+    const uint64_t i0 = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 8;
+    for (uint64_t i = i0; i < i0 + 8 && i < a.d; ++i) {
+        const uint32_t r = random_word(a.index_offset + i, a.first_worker + w, kDomainNat, a.k0, a.k1);
+        a.code_out[(size_t)w * a.code_stride + i] = (uint8_t)clip_byte(f32_bits(a.x[(size_t)w * a.x_stride + i]), ~r);
+    }
 }
 
 // binary32 bits of one byte: sign and 2^(field - 50), or a signed zero.
@@ -106,8 +107,8 @@ __global__ __launch_bounds__(kBlock) void clip_decode_kernel(const uint8_t* __re
 
 __global__ __launch_bounds__(kBlock) void clip_decode_generic_kernel(const uint8_t* __restrict__ code, uint64_t d,
                                                                      float* __restrict__ out) {
-    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (i < d) out[i] = bits_f32(clip_value_bits(code[i]));
+    const uint64_t i0 = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 8;
+    for (uint64_t i = i0; i < i0 + 8 && i < d; ++i) out[i] = bits_f32(clip_value_bits(code[i]));
 }
 
 // ------------------------------------------------------------------------ integer aggregation
@@ -234,7 +235,7 @@ hipError_t launch_clip_encode(const ClipEncodeArgs& a, uint32_t n, bool fast, hi
         const dim3 grid((unsigned)((a.d + kClipEncTile - 1) / kClipEncTile), n, 1);
         clip_encode_kernel<<<grid, kClipEncBlock, 0, stream>>>(a);
     } else {
-        const dim3 grid((unsigned)((a.d + kBlock - 1) / kBlock), n, 1);
+        const dim3 grid((unsigned)((a.d + 8 * kBlock - 1) / (8 * kBlock)), n, 1);
         clip_encode_generic_kernel<<<grid, kBlock, 0, stream>>>(a);
     }
     return hipGetLastError();
@@ -245,7 +246,7 @@ hipError_t launch_clip_decode(const uint8_t* code, uint64_t d, float* out, bool 
         const uint64_t groups = d / 8 + 1;  // the grid covers the ragged last group too
         clip_decode_kernel<<<(unsigned)((groups + kBlock - 1) / kBlock), kBlock, 0, stream>>>(code, d, out);
     } else {
-        clip_decode_generic_kernel<<<(unsigned)((d + kBlock - 1) / kBlock), kBlock, 0, stream>>>(code, d, out);
+        clip_decode_generic_kernel<<<(unsigned)((d + 8 * kBlock - 1) / (8 * kBlock)), kBlock, 0, stream>>>(code, d, out);
     }
     return hipGetLastError();
 }

@@ -479,7 +479,8 @@ void dither_bucket_encode_vec_kernel(DitherEncodeArgs a) {
 template <int BLOCK, int FMT, bool FAST>
 __global__ __launch_bounds__(BLOCK) void dither_bucket_encode_kernel(DitherEncodeArgs a) {
     __shared__ NormAcc scratch[BLOCK / 64];
-    const uint64_t begin = (uint64_t)blockIdx.x * a.segs.bucket;
+    const uint64_t bucket_index = a.first_bucket + blockIdx.x;
+    const uint64_t begin = bucket_index * a.segs.bucket;
     const uint64_t rest = a.segs.d - begin;
     const uint32_t len = rest < a.segs.bucket ? (uint32_t)rest : a.segs.bucket;
     const uint32_t l0 = threadIdx.x * 8;
@@ -491,11 +492,67 @@ __global__ __launch_bounds__(BLOCK) void dither_bucket_encode_kernel(DitherEncod
     for (int j = 0; j < 8; ++j) norm_add(acc, bits_f32(u[j]), a.pnorm);  // padding zeros add nothing
     acc = norm_block_reduce<BLOCK>(acc, a.pnorm, scratch);
     const float norm = norm_value(acc, a.pnorm);
-    if (threadIdx.x == 0) a.norms_out[blockIdx.x] = norm;
+    if (threadIdx.x == 0) a.norms_out[bucket_index] = norm;
     if (count == 0) return;
     const float iv = inv_of_norm(norm);
     const float inv[8] = {iv, iv, iv, iv, iv, iv, iv, iv};
     encode_group<FMT, FAST>(a, u, inv, begin + l0, count);
+}
+
+// One-pass encoder for power-of-two buckets (32 <= bucket <= 2048), vector path (same
+// alignment as the kernel above).  A workgroup takes a tile of 256 * QPL quads; a bucket of
+// W = bucket / 4 quads belongs to L = W / QPL consecutive lanes of one wavefront (8 <= L <= 64, a
+// power of two; buckets above 2048 are better served by the one-bucket-per-workgroup kernel
+// above), lane r of them holding quads r, r + L, ..., r + (QPL-1) L of the bucket, so every
+// load instruction reads runs of 16 L contiguous bytes and every aligned group of 8 lanes holds
+// 8 consecutive quads (what the packed stores need).  The norm is reduced inside the bucket's
+// lanes with xor-butterfly steps (no LDS, no barrier); the square root and the reciprocal are
+// computed once per lane for its QPL quads.  Only whole buckets are handled (`full_buckets` of
+// them); a ragged last bucket goes to the generic kernel.
+template <int QPL, int FMT>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6, 8)))
+void dither_pow2_bucket_encode_kernel(DitherEncodeArgs a, uint32_t log2_l, uint64_t full_buckets) {
+    const uint32_t lanes = 1u << log2_l;                   // L
+    const uint32_t b_local = threadIdx.x >> log2_l;        // bucket of this lane inside the tile
+    const uint32_t r = threadIdx.x & (lanes - 1u);
+    const uint32_t q_first = b_local * (lanes * QPL) + r;  // tile-local quad of k = 0
+    const uint64_t tile_quad0 = (uint64_t)blockIdx.x * (kBlock * QPL);
+    const uint64_t bucket_index = ((uint64_t)blockIdx.x << (8 - log2_l)) + b_local;
+    const bool have = bucket_index < full_buckets;         // the same for all lanes of a bucket
+    const u32x4* __restrict__ xv = reinterpret_cast<const u32x4*>(a.x) + tile_quad0;
+    u32x4 v[QPL];
+#pragma unroll
+    for (int k = 0; k < QPL; ++k) {
+        v[k] = u32x4{0u, 0u, 0u, 0u};
+        if (have) v[k] = load_stream(xv + q_first + k * lanes);
+    }
+    NormAcc acc = norm_zero();
+    norm_add_quads(acc, v, a.pnorm);
+    if (a.pnorm == kNormInf) {  // constant masks (cheap lane exchanges); steps 8, 16, 32 only for wider buckets
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1)
+            if (m < 8 || (uint32_t)m < lanes) acc.mx = fmaxf(acc.mx, __shfl_xor(acc.mx, m, 64));
+    } else {
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1)
+            if (m < 8 || (uint32_t)m < lanes) acc.sum += __shfl_xor(acc.sum, m, 64);
+    }
+    const float norm = norm_value(acc, a.pnorm);
+    if (have && r == 0) a.norms_out[bucket_index] = norm;
+    const float iv = inv_of_norm(norm);
+    const float iv4[4] = {iv, iv, iv, iv};
+    const LevelParams lp = level_params(a.s, a.standard);
+    const uint64_t tile_elem0 = tile_quad0 * 4;
+    const uint64_t q_global = (a.index_offset >> 2) + tile_quad0;
+    uint32_t* __restrict__ code_base =
+        reinterpret_cast<uint32_t*>(a.code_out + (FMT == kFmtByte ? tile_elem0 : tile_elem0 >> 1));
+    uint32_t* __restrict__ sign_base = reinterpret_cast<uint32_t*>(a.sign_out + (tile_elem0 >> 3));
+#pragma unroll
+    for (int k = 0; k < QPL; ++k) {
+        const uint32_t q = q_first + k * lanes;
+        encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, q_global + q, have);
+        __builtin_amdgcn_sched_barrier(0);  // one quad at a time keeps the register count low
+    }
 }
 
 // Adds to acc the lane's elements that fall into the chunk-local piece [lb, le); the lane
@@ -670,7 +727,8 @@ __global__ __launch_bounds__(kBlock) void dither_segment_encode_kernel(DitherEnc
     SegHit hit;
     if (a.chunk_segment) {  // segment offsets: the norm pass left one record per chunk
         const ChunkSegment rec = a.chunk_segment[blockIdx.x];
-        hit = SegHit{rec.segment, rec.inv_norm, 0ull, rec.end};
+        // (offsets that do not cover [0, d) leave records unwritten: keep the index in range)
+        hit = SegHit{min(rec.segment, sg.num_segments - 1), rec.inv_norm, 0ull, rec.end};
     } else {
         hit = seg_find_block(sg, cb, a.inv_norm, &slot);  // arithmetic on the bucket size
     }
@@ -762,12 +820,13 @@ __device__ __forceinline__ void dither_load_codes(const DitherAggregateArgs& a, 
     }
 }
 // Each of the lane's 8 elements looks its value up in the workers' 16-entry tables and adds it.
+// `rows` is the lane's table of table-worker 0 and row_stride the distance to the next worker's.
 template <int FMT, int NW>
-__device__ __forceinline__ void dither_add_codes(const float* table, uint32_t w_table, const uint32_t cw[NW],
-                                                 const uint32_t sb[NW], float acc[8]) {
+__device__ __forceinline__ void dither_add_codes(const float* rows, uint32_t row_stride, uint32_t w_table,
+                                                 const uint32_t cw[NW], const uint32_t sb[NW], float acc[8]) {
 #pragma unroll
     for (int k = 0; k < NW; ++k) {
-        const float* row = table + (w_table + k) * 16;
+        const float* row = rows + (w_table + k) * row_stride;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             float v = row[(cw[k] >> (4 * j)) & 15u];
@@ -777,11 +836,11 @@ __device__ __forceinline__ void dither_add_codes(const float* table, uint32_t w_
     }
 }
 template <int FMT, int NW>
-__device__ __forceinline__ void dither_sum_chunk(const DitherAggregateArgs& a, const float* table, uint64_t grp,
-                                                 uint32_t w_table, size_t w_global, float acc[8]) {
+__device__ __forceinline__ void dither_sum_chunk(const DitherAggregateArgs& a, const float* rows, uint32_t row_stride,
+                                                 uint64_t grp, uint32_t w_table, size_t w_global, float acc[8]) {
     uint32_t cw[NW], sb[NW];
     dither_load_codes<FMT, NW>(a, grp, w_global, cw, sb);
-    dither_add_codes<FMT, NW>(table, w_table, cw, sb, acc);
+    dither_add_codes<FMT, NW>(rows, row_stride, w_table, cw, sb, acc);
 }
 
 // One element of the sum by plain arithmetic (any layout and alignment).
@@ -806,14 +865,17 @@ __device__ __forceinline__ float dither_sum_one(const DitherAggregateArgs& a, ui
 
 // Decode (n = 1) and fused decode-and-sum.  One lane owns 8 consecutive output elements;
 // results leave through the LDS transpose (VEC: out 16-byte aligned, code planes 4-byte
-// aligned with 4-byte-multiple strides).  Nibble formats in a chunk that lies inside one
-// segment use tables: for up to 16 workers at a time the workgroup tabulates in LDS the 16
-// values a nibble can decode to (fused format: sign included), so an element costs one
-// bit-field extract, one LDS read and one add per worker.  Everything else (byte codes,
-// chunks that straddle segments) is decoded arithmetically: norm * 2^(c-s).
-template <int FMT, bool VEC>
+// aligned with 4-byte-multiple strides).  Nibble formats use tables: for up to 16 workers at a
+// time the workgroup tabulates in LDS the 16 values a nibble can decode to (fused format: sign
+// included), so an element costs one bit-field extract, one LDS read and one add per worker.
+// TABLE = 256 floats: one table per worker, for chunks that lie inside one segment.
+// TABLE = 4096 floats: power-of-two buckets of 64..1024 elements (a.log2_bucket), one table per
+// (worker, bucket of the chunk); a lane's 8 elements share a bucket.  Everything else (byte
+// codes, chunks that straddle other segment boundaries) is decoded arithmetically:
+// norm * 2^(c-s).
+template <int FMT, bool VEC, int TABLE>
 __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregateArgs a) {
-    __shared__ float table[16 * 16];
+    __shared__ float table[TABLE];
     __shared__ u32x4 tile[2 * kBlock];
     __shared__ SegHit slot;
     __shared__ uint32_t bnd[kBlock];
@@ -826,27 +888,41 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
     // The first (up to 8) workers' codes do not depend on the segment: load them before the
     // segment search and the table, so the two global round trips overlap.
     constexpr bool kTables = VEC && FMT != kFmtByte;
+    constexpr bool kMulti = TABLE > 256;
     const uint32_t n_first = a.n >= 8 ? 8u : (a.n == 1 ? 1u : 0u);  // 2..7 workers: no preload
     uint32_t cw0[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u}, sb0[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
     if (kTables && count == 8) {
         if (n_first == 8) dither_load_codes<FMT, 8>(a, grp, 0, cw0, sb0);
         else if (n_first == 1) dither_load_codes<FMT, 1>(a, grp, 0, cw0, sb0);
     }
-    const SegHit hit = seg_find_block(sg, cb, nullptr, &slot);
-    const uint32_t s0 = hit.s;
-    const bool one_segment = hit.end >= ce;
+    uint32_t s0, log2_nbk = 0, lane_bucket = 0, nseg = 0;
+    bool one_segment;
+    if (kMulti) {  // the chunk holds 2^log2_nbk whole buckets, the first of index s0
+        log2_nbk = 11u - a.log2_bucket;  // kChunk = 2^11
+        s0 = blockIdx.x << log2_nbk;
+        lane_bucket = (threadIdx.x * 8u) >> a.log2_bucket;
+        nseg = (uint32_t)((sg.d + sg.bucket - 1) >> a.log2_bucket);
+        one_segment = true;  // (for the table path: every lane's elements have a table)
+    } else {
+        const SegHit hit = seg_find_block(sg, cb, nullptr, &slot);
+        s0 = hit.s;
+        one_segment = hit.end >= ce;
+    }
+    const uint32_t nbk = 1u << log2_nbk;
+    const uint32_t rounds_of = (kMulti && nbk > 16u) ? (uint32_t)(TABLE / 16) >> log2_nbk : 16u;  // workers per table round
+    const float* rows = table + lane_bucket * 16u;
+    const uint32_t row_stride = nbk * 16u;
     float acc[8] = {-0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f};
 
     if (kTables && one_segment) {
-        for (uint32_t w0 = 0; w0 < a.n; w0 += 16) {
-            const uint32_t nw = a.n - w0 < 16 ? a.n - w0 : 16u;
-            {   // tabulate: entry (worker, nibble)
-                const uint32_t w = threadIdx.x >> 4, nib = threadIdx.x & 15u;
-                if (w < nw) {
-                    const float norm = a.norms[(size_t)(w0 + w) * a.norm_stride + s0];
-                    table[threadIdx.x] = (FMT == kFmtFused) ? dither_value(norm, a.s, nib & 7u, nib >> 3, a.standard)
-                                                           : dither_value(norm, a.s, nib, 0u, a.standard);
-                }
+        for (uint32_t w0 = 0; w0 < a.n; w0 += rounds_of) {
+            const uint32_t nw = a.n - w0 < rounds_of ? a.n - w0 : rounds_of;
+            // tabulate: entry ((worker, bucket), nibble)
+            for (uint32_t e = threadIdx.x; e < (nw << (4u + log2_nbk)); e += kBlock) {
+                const uint32_t w = e >> (4u + log2_nbk), seg = s0 + ((e >> 4) & (nbk - 1u)), nib = e & 15u;
+                const float norm = (!kMulti || seg < nseg) ? a.norms[(size_t)(w0 + w) * a.norm_stride + seg] : 0.0f;
+                table[e] = (FMT == kFmtFused) ? dither_value(norm, a.s, nib & 7u, nib >> 3, a.standard)
+                                              : dither_value(norm, a.s, nib, 0u, a.standard);
             }
             __syncthreads();
             if (count == 8) {
@@ -856,19 +932,20 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
                     // computed ahead of the barrier and the kernel loses half its wavefronts
 #pragma unroll
                     for (int k = 0; k < 8; ++k) asm volatile("" : "+v"(cw0[k]), "+v"(sb0[k]));
-                    if (n_first == 8) dither_add_codes<FMT, 8>(table, 0, cw0, sb0, acc);
-                    else if (n_first == 1) dither_add_codes<FMT, 1>(table, 0, cw0, sb0, acc);
+                    if (n_first == 8) dither_add_codes<FMT, 8>(rows, row_stride, 0, cw0, sb0, acc);
+                    else if (n_first == 1) dither_add_codes<FMT, 1>(rows, row_stride, 0, cw0, sb0, acc);
                     w = n_first;
                 }
-                for (; w + 8 <= nw; w += 8) dither_sum_chunk<FMT, 8>(a, table, grp, w, w0 + w, acc);
-                for (; w + 2 <= nw; w += 2) dither_sum_chunk<FMT, 2>(a, table, grp, w, w0 + w, acc);
-                if (w < nw) dither_sum_chunk<FMT, 1>(a, table, grp, w, w0 + w, acc);
+                for (; w + 8 <= nw; w += 8) dither_sum_chunk<FMT, 8>(a, rows, row_stride, grp, w, w0 + w, acc);
+                for (; w + 2 <= nw; w += 2) dither_sum_chunk<FMT, 2>(a, rows, row_stride, grp, w, w0 + w, acc);
+                if (w < nw) dither_sum_chunk<FMT, 1>(a, rows, row_stride, grp, w, w0 + w, acc);
             }
             __syncthreads();
         }
         if (count > 0 && count < 8) {  // the ragged last group of the vector
 #pragma unroll
-            for (int j = 0; j < 8; ++j) if ((uint32_t)j < count) acc[j] = dither_sum_one<FMT>(a, i0 + j, s0);
+            for (int j = 0; j < 8; ++j)
+                if ((uint32_t)j < count) acc[j] = dither_sum_one<FMT>(a, i0 + j, s0 + lane_bucket);
         }
     } else {
         const uint32_t nb = one_segment ? 0u : stage_boundaries(sg, cb, ce, s0, bnd);  // block-uniform
@@ -954,6 +1031,18 @@ __global__ __launch_bounds__(kBlock) void dither_decode_kernel(DitherAggregateAr
             if (FMT == kFmtNibble) v |= (sb << (31 - j)) & 0x80000000u;
             bits[j] = v;
         }
+    } else if (!sg.offsets && (sg.bucket & 7u) == 0 && sg.bucket <= (1u << 20)) {
+        // buckets that are a multiple of 8: the lane's 8 elements share one bucket, whose index
+        // follows from the position alone (no search, so the norm load is not behind a barrier)
+        const uint32_t seg = s0 + ((uint32_t)(cb - hit.begin) + l0) / sg.bucket;
+        const float norm = a.norms[seg < seg_count(sg) ? seg : s0];  // (lanes past the end: any valid index)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t nib = (cw >> (4 * j)) & 15u;
+            const uint32_t c = (FMT == kFmtFused) ? (nib & 7u) : nib;
+            const uint32_t sgn = (FMT == kFmtFused) ? (nib >> 3) : ((sb >> j) & 1u);
+            bits[j] = f32_bits(dither_value(norm, a.s, c, sgn, a.standard));
+        }
     } else {
         const uint32_t nb = stage_boundaries(sg, cb, ce, s0, bnd);  // block-uniform branch
         SegCursor cur;
@@ -1034,8 +1123,42 @@ static hipError_t launch_bucket_vec(const DitherEncodeArgs& a, unsigned grid, hi
     return hipGetLastError();
 }
 
+template <int QPL>
+static void launch_pow2(const DitherEncodeArgs& a, uint32_t log2_l, uint64_t full, unsigned tiles, hipStream_t st) {
+    switch (a.fmt) {
+        case kFmtFused: dither_pow2_bucket_encode_kernel<QPL, kFmtFused><<<tiles, kBlock, 0, st>>>(a, log2_l, full); break;
+        case kFmtNibble: dither_pow2_bucket_encode_kernel<QPL, kFmtNibble><<<tiles, kBlock, 0, st>>>(a, log2_l, full); break;
+        default: dither_pow2_bucket_encode_kernel<QPL, kFmtByte><<<tiles, kBlock, 0, st>>>(a, log2_l, full); break;
+    }
+}
+
 hipError_t launch_dither_bucket_encode(const DitherEncodeArgs& a, bool fast, hipStream_t stream) {
     const unsigned grid = (unsigned)((a.segs.d + a.segs.bucket - 1) / a.segs.bucket);
+    const uint32_t bucket = a.segs.bucket;
+    if (fast && bucket >= 32 && bucket <= 2048 && (bucket & (bucket - 1)) == 0) {
+        // power-of-two buckets: QPL quads per lane, L = bucket / 4 / QPL lanes per bucket (>= 8)
+        const uint32_t quads = bucket / 4;
+        // measured best: runs of at least 256 contiguous bytes per load where the bucket allows it
+        const int qpl = quads <= 8 ? 1 : quads <= 32 ? 2 : quads <= 128 ? 4 : 8;
+        uint32_t log2_l = 0;
+        while ((qpl << log2_l) < quads) ++log2_l;
+        const uint64_t full = a.segs.d / bucket;
+        if (full) {
+            const unsigned tiles = (unsigned)((full * quads + (uint64_t)kBlock * qpl - 1) / ((uint64_t)kBlock * qpl));
+            switch (qpl) {
+                case 1: launch_pow2<1>(a, log2_l, full, tiles, stream); break;
+                case 2: launch_pow2<2>(a, log2_l, full, tiles, stream); break;
+                case 4: launch_pow2<4>(a, log2_l, full, tiles, stream); break;
+                default: launch_pow2<8>(a, log2_l, full, tiles, stream); break;
+            }
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        if (full * bucket == a.segs.d) return hipSuccess;
+        DitherEncodeArgs tail = a;  // the ragged last bucket, one workgroup
+        tail.first_bucket = full;
+        return launch_bucket<256, false>(tail, 1, stream);  // 256 lanes x 8 elements cover a bucket of 2048
+    }
     if (fast && (a.segs.bucket & 31) == 0) {  // vector path: 256 lanes, QPL quads per lane
         const uint32_t quads = a.segs.bucket / 4;
         if (quads <= 256) return launch_bucket_vec<1>(a, grid, stream);
@@ -1081,10 +1204,19 @@ static hipError_t launch_agg(const DitherAggregateArgs& a, hipStream_t st) {
         else dither_decode_kernel<kFmtNibble><<<chunks, kBlock, 0, st>>>(a);
         return hipGetLastError();
     }
+    const uint32_t bucket = a.segs.bucket;
+    if (FAST && a.fmt != kFmtByte && !a.segs.offsets && bucket >= 64 && bucket <= 1024 && (bucket & (bucket - 1)) == 0) {
+        DitherAggregateArgs b = a;  // several whole buckets per chunk: tables per (worker, bucket)
+        b.log2_bucket = 6;
+        while ((1u << b.log2_bucket) < bucket) ++b.log2_bucket;
+        if (a.fmt == kFmtFused) dither_aggregate_kernel<kFmtFused, FAST, 4096><<<chunks, kBlock, 0, st>>>(b);
+        else dither_aggregate_kernel<kFmtNibble, FAST, 4096><<<chunks, kBlock, 0, st>>>(b);
+        return hipGetLastError();
+    }
     switch (a.fmt) {
-        case kFmtFused: dither_aggregate_kernel<kFmtFused, FAST><<<chunks, kBlock, 0, st>>>(a); break;
-        case kFmtNibble: dither_aggregate_kernel<kFmtNibble, FAST><<<chunks, kBlock, 0, st>>>(a); break;
-        default: dither_aggregate_kernel<kFmtByte, FAST><<<chunks, kBlock, 0, st>>>(a); break;
+        case kFmtFused: dither_aggregate_kernel<kFmtFused, FAST, 256><<<chunks, kBlock, 0, st>>>(a); break;
+        case kFmtNibble: dither_aggregate_kernel<kFmtNibble, FAST, 256><<<chunks, kBlock, 0, st>>>(a); break;
+        default: dither_aggregate_kernel<kFmtByte, FAST, 256><<<chunks, kBlock, 0, st>>>(a); break;
     }
     return hipGetLastError();
 }

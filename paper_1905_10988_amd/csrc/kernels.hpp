@@ -55,11 +55,13 @@ struct DitherEncodeArgs {
     double* head_partial;    // one per segment    (two-pass path only)
     float* inv_norm;         // one per segment    (two-pass path only)
     ChunkSegment* chunk_segment;  // one per kChunk elements (two-pass path with segment offsets only)
+    uint64_t first_bucket;        // generic one-pass kernel: index of the bucket workgroup 0 encodes
 };
 struct DitherAggregateArgs {
     const float* norms; size_t norm_stride; const uint8_t* code; size_t code_stride;
     const uint8_t* sign; size_t sign_stride;
     uint32_t n; Segs segs; uint32_t s; int fmt; uint32_t standard; float* out;
+    uint32_t log2_bucket;   // set by the launcher for the kernel with per-bucket tables
 };
 
 // One-pass encoder for fixed buckets of at most kMaxOnePassBucket elements (a multiple of 8).

@@ -103,6 +103,18 @@ def test_layer_segments(nc, oracle, wl):
     roundtrip(nc, oracle, x, 2, 8, offsets=np.array([0, d], np.uint64))
 
 
+@pytest.mark.parametrize("bucket", [32, 64, 128, 256, 512, 1024, 2048, 4096, 8192])
+def test_power_of_two_buckets(nc, oracle, wl, bucket):
+    """The kernel that gives a bucket to 8..256 lanes of a workgroup: whole tiles, a partial
+    last tile, a ragged last bucket (also one that is not a multiple of 8), a vector shorter
+    than one bucket; all three code formats and norms; a non-zero index offset."""
+    for d in (4 * max(bucket, 2048), 2048 + 3 * bucket, 5 * 2048 + bucket + 40, 7 * bucket + 13, bucket - 5):
+        x = wl.bucketed_gaussian(1, d=d, bucket=bucket, seed=60 + bucket % 7)
+        for p, s in [(INF, 4), (2, 8), (1, 20)]:
+            roundtrip(nc, oracle, x, p, s, bucket=bucket)
+        roundtrip(nc, oracle, x, 2, 8, bucket=bucket, index_offset=2**33 + 8, worker=3)
+
+
 @pytest.mark.parametrize("max_len", [9, 40, 700])
 def test_many_small_segments(nc, oracle, wl, max_len):
     """Segments of 0..max_len elements: hundreds of boundaries in one chunk (more than the
@@ -205,7 +217,20 @@ def test_dithering_reduces_to_natural_compression_on_gpu(nc, oracle):
 @pytest.mark.parametrize("n", [1, 2, 8, 9, 16, 17, 33])
 @pytest.mark.parametrize("s,p", [(4, INF), (8, 2), (20, 1)])
 def test_aggregate(nc, oracle, wl, n, s, p):
-    d, bucket = 3 * 8192 + 1001, 8192
+    aggregate_case(nc, oracle, wl, n, s, p, d=3 * 8192 + 1001, bucket=8192)
+
+
+@pytest.mark.parametrize("bucket", [32, 64, 128, 256, 512, 1024, 2048, 96, 1000])
+@pytest.mark.parametrize("n", [2, 8, 19])
+def test_aggregate_small_buckets(nc, oracle, wl, n, bucket):
+    """Several buckets per 2048-element chunk: per-(worker, bucket) tables for powers of two from
+    64 to 1024, the arithmetic path otherwise; whole chunks, a partial last chunk, a ragged end."""
+    for s, p in [(4, INF), (8, 2)]:
+        aggregate_case(nc, oracle, wl, n, s, p, d=3 * 2048 + 5 * bucket + 13, bucket=bucket)
+    aggregate_case(nc, oracle, wl, n, 20, 1, d=2 * 2048 + bucket + 8, bucket=bucket)
+
+
+def aggregate_case(nc, oracle, wl, n, s, p, d, bucket):
     xs = [wl.bucketed_gaussian(w, d=d, bucket=bucket, seed=17) for w in range(n)]
     nseg = nc.segment_count(d, 0, bucket, False)
     cs, ss = nc.plane_stride(nc.dither_code_bytes(d, s)), nc.plane_stride(max(nc.dither_sign_bytes(d, s), 1))
