@@ -104,7 +104,23 @@ def secondary_kernels(nc, wl, torch, np):
         "this two-pass path moves 8 + 0.625 unless the second read hits the last-level cache")
     ms = _time_ms(torch, np, lambda: nc.dither_decode(norms, code, sign, d, 8, seg_offsets=offdev, out=out))
     res["config3_dither_2_8_layer_decode"] = _entry(ms, 4.625 * d, 4.0 * d, "0.625 B read + 4 B written per element")
-    del x, out, code, sign, e, sg
+    # D_nat^{inf,4} with small buckets (512 elements, the usual choice of QSGD-style bucketing): one-pass encode
+    # of one worker and the fused sum of 8 workers, d = 25.6 M
+    nw, b512 = wl.NUM_WORKERS, 512
+    nb512 = nc.segment_count(d, 0, b512, False)
+    norms5 = torch.empty((nw, nb512), dtype=torch.float32, device="cuda")
+    code5 = torch.empty((nw, nc.plane_stride(nc.dither_code_bytes(d, 4))), dtype=torch.uint8, device="cuda")
+    for w in range(nw):
+        nc.dither_encode(x, math.inf, 4, 0, worker=w, bucket=b512, norms_out=norms5[w], code_out=code5[w])
+    ms = _time_ms(torch, np, lambda: nc.dither_encode(x, math.inf, 4, 0, bucket=b512, norms_out=norms5[0],
+                                                      code_out=code5[0]))
+    res["dither_inf_4_bucket512_encode_d25.6M"] = _entry(ms, 4.5 * d + 4.0 * nb512, 4.0 * d,
+                                                        "one pass, 8 buckets per workgroup; 4 + 0.5 B per element")
+    ms = _time_ms(torch, np, lambda: nc.aggregate_sum(nc.NC_KIND_DITHER, d, code5, None, norms5, s=4, bucket=b512,
+                                                      out=out))
+    res["dither_inf_4_bucket512_aggregate_n8_d25.6M"] = _entry(ms, 8.0 * d + 4.0 * nb512 * nw, 4.0 * d * nw,
+                                                              "per-(worker, bucket) tables; 8 x 0.5 B read + 4 B written")
+    del x, out, code, sign, e, sg, norms5, code5
     # config 4: D_nat^{inf,4}, buckets of 8192, 8 workers, fused decode+sum
     d4, n, bucket = wl.D_VGG16, wl.NUM_WORKERS, wl.BUCKET
     nb = nc.segment_count(d4, 0, bucket, False)
