@@ -38,6 +38,12 @@ def lib():
         L.orc_clip_decode.restype = None
         L.orc_clip_aggregate.argtypes = [_u8p, _u64, _u32, _u64, _u64, _u32, _u64, _i64p, _u8p, _u8p]
         L.orc_clip_aggregate.restype = None
+        L.orc_clip_round.argtypes = [ctypes.c_int64, _u32]
+        L.orc_clip_round.restype = _u32
+        L.orc_clip_count_up.argtypes = [ctypes.c_int64]
+        L.orc_clip_count_up.restype = _u64
+        L.orc_find_word_below.argtypes = [_u64, _u32, _u32, _u64, _u64, _u32]
+        L.orc_find_word_below.restype = ctypes.c_int64
         L.orc_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
         L.orc_philox4x32_10.restype = None
         L.orc_random_word.argtypes = [_u64, _u32, _u32, _u64]
@@ -420,3 +426,18 @@ def clip_aggregate(code, d, seed, master=0, index_offset=0):
     lib().orc_clip_aggregate(_ptr(code, _u8p), code.shape[1], code.shape[0], d, seed, master, index_offset,
                              _ptr(total, _i64p), _ptr(e, _u8p), _ptr(s, _u8p))
     return total, e, s
+
+
+def clip_round(total, r):
+    """Exponent field of C_nat(total * 2^-50) for the word r (0 for total = 0)."""
+    return lib().orc_clip_round(total, r)
+
+
+def clip_count_up(total):
+    """Number of words r, out of 2^32, that round |total| up to the next power of two."""
+    return lib().orc_clip_count_up(total)
+
+
+def find_word_below(seed, worker, domain, start, count, bound):
+    """First global index in [start, start + count) whose random word is below `bound`, or -1."""
+    return lib().orc_find_word_below(seed, worker, domain, start, count, bound)

@@ -727,6 +727,42 @@ void orc_clip_decode(const uint8_t *code, uint64_t d, float *out)
  * lost to truncation.  Outputs: sum_out[i] (may be NULL) in units of 2^-50; the
  * planes of orc_nat_encode for the compressed sum, exponent field k - 50 + 127
  * (+1), 0 for S = 0; sign bit set for S < 0. */
+/* C_nat of one integer sum (two's complement in `total`) with the word r: the
+ * exponent field of the result, 0 for a zero sum. */
+uint32_t orc_clip_round(int64_t total_signed, uint32_t r)
+{
+    uint64_t total = (uint64_t)total_signed;
+    uint64_t mag = (total >> 63) ? (0ull - total) : total;
+    if (mag == 0) return 0;
+    int k = 63;
+    while (!((mag >> k) & 1ull)) --k;
+    uint64_t rest = mag - (1ull << k);  /* < 2^k */
+    /* floor(rest / 2^k * 2^32) */
+    uint64_t threshold = k >= 32 ? (rest >> (k - 32)) : (rest << (32 - k));
+    return (uint32_t)(k - 50 + 127) + (((uint64_t)r < threshold) ? 1u : 0u);
+}
+
+/* Exhaustive count of "exponent + 1" outcomes over all 2^32 words r. */
+uint64_t orc_clip_count_up(int64_t total)
+{
+    uint32_t low = orc_clip_round(total, 0xFFFFFFFFu);
+    uint64_t count = 0;
+#pragma omp parallel for reduction(+ : count)
+    for (int64_t r = 0; r < ((int64_t)1 << 32); ++r)
+        count += (orc_clip_round(total, (uint32_t)r) != low);
+    return count;
+}
+
+/* First global index g in [start, start + count) whose word is below `bound`,
+ * or -1 (lets a test place a chosen sum on an element whose word it knows). */
+int64_t orc_find_word_below(uint64_t seed, uint32_t worker, uint32_t domain, uint64_t start, uint64_t count,
+                            uint32_t bound)
+{
+    for (uint64_t g = start; g < start + count; ++g)
+        if (orc_random_word(seed, worker, domain, g) < bound) return (int64_t)g;
+    return -1;
+}
+
 void orc_clip_aggregate(const uint8_t *code, uint64_t code_stride, uint32_t n, uint64_t d, uint64_t seed,
                         uint32_t master, uint64_t index_offset, int64_t *sum_out, uint8_t *exp_out,
                         uint8_t *sign_out)
@@ -737,18 +773,8 @@ void orc_clip_aggregate(const uint8_t *code, uint64_t code_stride, uint32_t n, u
         for (uint32_t w = 0; w < n; ++w) total += clip_units(code[(uint64_t)w * code_stride + i]);
         if (sum_out) sum_out[i] = (int64_t)total;
         uint32_t negative = (uint32_t)(total >> 63);
-        uint64_t mag = negative ? (0ull - total) : total;
-        uint32_t e = 0;
-        if (mag != 0) {
-            int k = 63;
-            while (!((mag >> k) & 1ull)) --k;
-            uint64_t rest = mag - (1ull << k);  /* < 2^k */
-            /* floor(rest / 2^k * 2^32) */
-            uint64_t threshold = k >= 32 ? (rest >> (k - 32)) : (rest << (32 - k));
-            uint32_t r = orc_random_word(seed, master, ORC_DOMAIN_MASTER, index_offset + i);
-            e = (uint32_t)(k - 50 + 127) + (((uint64_t)r < threshold) ? 1u : 0u);
-        }
-        exp_out[i] = (uint8_t)e;
+        uint32_t r = orc_random_word(seed, master, ORC_DOMAIN_MASTER, index_offset + i);
+        exp_out[i] = (uint8_t)orc_clip_round((int64_t)total, r);
         sign_out[i >> 3] |= (uint8_t)(negative << (i & 7));
     }
 }

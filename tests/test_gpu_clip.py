@@ -197,3 +197,25 @@ def test_errors(nc):
         nc._check(nc.lib().nc_clip_aggregate_int(code.data_ptr(), 50, 2, 100, 0, 0, 0, None, code.data_ptr(),
                                                  code.data_ptr(), None))
     assert nc.nat_clip_encode(x[:0], 0).numel() == 0
+
+
+def test_word_equal_to_threshold_stays_on_gpu(nc, oracle):
+    """The comparison in the master's rounding is strict: an element whose random word r is known
+    carries the sum 2^60 + r 2^28 (threshold = r) and must stay at 2^60, both in the vector path
+    and in the any-alignment path; with one more unit of 2^28 it goes up."""
+    seed, master = 123, 2
+    g = oracle.find_word_below(seed, master, 3, 0, 1 << 22, 1 << 12)
+    r = oracle.random_word(seed, master, 3, g)
+    assert g >= 0 and 0 < r < (1 << 12)
+    for extra, up in [(0, 0), (1, 1)]:
+        units = (1 << 60) + ((r + extra) << 28)
+        bits = [b for b in range(64) if (units >> b) & 1]
+        for d, pos, off in [(64, g % 4, g - g % 4), (64, 37, g - 37), (5, 2, g - 2)]:
+            if off < 0:
+                continue
+            code = np.full((len(bits), d), 0x40, np.uint8)
+            code[:, pos] = bits
+            sums, e, s = nc.clip_aggregate_int(dev(code), d, seed, master=master, index_offset=off, want_sum=True)
+            so, eo, sgo = oracle.clip_aggregate(code, d, seed, master, off)
+            assert np.array_equal(host(sums), so) and np.array_equal(host(e), eo) and np.array_equal(host(s), sgo)
+            assert int(host(sums)[pos]) == units and int(host(e)[pos]) == 60 + 77 + up

@@ -126,3 +126,31 @@ def test_matches_binary32_master_on_exact_sums(oracle):
     assert np.array_equal(e[nz], e32[nz]) and (e[~nz] == 0).all() and (e32[~nz] == 0).all()
     assert np.array_equal(s, s32)
     assert nz.sum() > d // 2 and (e != (np.floor(np.log2(np.abs(total) + (total == 0))) + 77))[nz].any()
+
+
+def test_rounding_counts_exhaustive(oracle):
+    """All 2^32 words: 5 * 2^57 goes up for exactly 2^30 of them and 2^60 + 2^28 for exactly one
+    (r = 0); for other sums the two words next to the threshold decide (strict comparison)."""
+    assert oracle.clip_count_up(5 << 57) == 1 << 30
+    assert oracle.clip_count_up((1 << 60) + (1 << 28)) == 1
+    for total, k, threshold in [(5 << 7, 9, 1 << 30), (3 << 40, 41, 1 << 31), (-7, 2, 3 << 30), (-(9 << 20), 23, 1 << 29)]:
+        assert oracle.clip_round(total, threshold - 1) == k + 77 + 1
+        assert oracle.clip_round(total, threshold) == k + 77         # r = threshold stays
+        assert oracle.clip_round(total, 0) == k + 77 + 1 and oracle.clip_round(total, TWO32 - 1) == k + 77
+    for r in (0, 1, TWO32 - 1):
+        assert oracle.clip_round(1 << 33, r) == 33 + 77 and oracle.clip_round(0, r) == 0
+
+
+def test_word_equal_to_threshold_stays(oracle):
+    """An element whose word r is known and small gets the sum 2^60 + r 2^28, whose threshold is r
+    itself: it must stay at 2^60; one more unit of 2^28 and it goes up."""
+    seed, master = 123, 2
+    g = oracle.find_word_below(seed, master, DOMAIN_MASTER, 0, 1 << 22, 1 << 12)
+    assert g >= 0
+    r = oracle.random_word(seed, master, DOMAIN_MASTER, g)
+    assert 0 < r < (1 << 12)
+    for extra, up in [(0, 0), (1, 1)]:
+        units = (1 << 60) + ((r + extra) << 28)
+        code = _codes_for([units])
+        total, e, s = oracle.clip_aggregate(code, 1, seed, master, index_offset=g)
+        assert int(total[0]) == units and e[0] == 60 + 77 + up and s[0] == 0
