@@ -342,3 +342,42 @@ def test_compressed_norm(nc, oracle, wl):
     e2, q2 = nc.norm_compress(dev(edge), seed=1)
     eo2, qo2 = oracle.norm_compress(edge, 1)
     assert np.array_equal(host(e2), eo2) and np.array_equal(host(q2).view(np.uint32), qo2.view(np.uint32))
+
+
+@pytest.mark.parametrize("s", [4, 8, 100])
+def test_words_at_the_threshold(nc, oracle, s):
+    """Inputs built from the random words (max-norm 1, so y = |x|): in the geometric region a
+    mantissa equal to the top 23 bits of the element's word stays and one more goes up; below the
+    lowest level y = r 2^-(s+31) has threshold r (stays at 0) and (r + 256) 2^-(s+31) goes to the
+    lowest level.  Whole vector in one segment (two-pass path) and bucketed (one-pass path)."""
+    d, seed, worker, off = 3 * 8192, 31, 2, 8
+    rng = np.random.default_rng(2)
+    r = np.array([oracle.random_word(seed, worker, oracle.DOMAIN_DITHER, off + i) for i in range(d)], np.uint64)
+    sign = rng.integers(0, 2, d).astype(np.uint32)
+    k = rng.integers(1, s, d).astype(np.uint32)                 # y in [2^-k, 2^(1-k)), 1 <= k <= s-1
+    m_stay = (r >> np.uint64(9)).astype(np.uint32)
+    linear = ((r & np.uint64(255)) == 0) & (r > 0)              # words with at most 24 significant bits
+    linear[::512] = False                                       # (these positions hold the buckets' maxima)
+    assert linear.sum() > 20
+    for bump, up in [(0, 0), (1, 1)]:
+        ok = m_stay + bump < (1 << 23)
+        m = np.where(ok, m_stay + bump, m_stay)
+        x = ((sign << 31) | ((127 - k) << 23) | m).astype(np.uint32).view(np.float32)
+        t = (r[linear] + np.uint64(256 * bump)).astype(np.float64)
+        x[linear] = (np.ldexp(t, -(s + 31)) * np.where(sign[linear] == 1, -1.0, 1.0)).astype(np.float32)
+        x[::512] = 1.0                                           # every bucket's max-norm is 1
+        expect = (s - k + up).astype(np.int64)
+        expect[linear] = up
+        geo = ok & ~linear
+        geo[::512] = False
+        for bucket in (0, 8192, 512):
+            norms, code, _ = roundtrip(nc, oracle, x, INF, s, seed=seed, worker=worker, index_offset=off, bucket=bucket)
+            assert np.all(norms == 1.0)
+            if s <= 7:
+                c = ((code[np.arange(d) // 2] >> (4 * (np.arange(d) & 1))) & 7).astype(np.int64)
+            elif s <= 15:
+                c = ((code[np.arange(d) // 2] >> (4 * (np.arange(d) & 1))) & 15).astype(np.int64)
+            else:
+                c = code.astype(np.int64)
+            assert np.array_equal(c[geo], expect[geo])
+            assert np.array_equal(c[linear], expect[linear])

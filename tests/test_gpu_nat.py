@@ -232,3 +232,41 @@ def test_master_compression_config2_full_size(nc, oracle, wl):
         sw = host(sign[:, a // 8: b // 8]).copy()
         _, eo, so = oracle.master_nat(ew, sw, b - a, 1, 0, index_offset=a)
         assert np.array_equal(eh[a:b], eo) and np.array_equal(sh[a // 8: b // 8], so)
+
+
+@pytest.mark.parametrize("index_offset", [0, 5, 2**33 + 4])
+def test_words_at_the_threshold(nc, oracle, index_offset):
+    """Inputs built from the random words themselves: a mantissa equal to the top 23 bits of the
+    element's word sits exactly at the comparison boundary (r >= m 2^9: stays), one more goes up.
+    Random data almost never lands there, so this pins the strict comparison in the kernels
+    (vector and any-alignment paths, worker and master streams)."""
+    d, seed, worker = 4096 + 37, 77, 3
+    rng = np.random.default_rng(1)
+    r = np.array([oracle.random_word(seed, worker, 0, index_offset + i) for i in range(d)], np.uint64)
+    e = rng.integers(1, 255, d).astype(np.uint32)
+    sign = rng.integers(0, 2, d).astype(np.uint32)
+    m_stay = (r >> 9).astype(np.uint32)
+    for bump, up in [(0, 0), (1, 1)]:
+        ok = m_stay + bump < (1 << 23)
+        m = np.where(ok, m_stay + bump, m_stay)
+        x = ((sign << 31) | (e << 23) | m).astype(np.uint32).view(np.float32)
+        _, _, eo, _ = encode_checked(nc, oracle, x, seed, worker, index_offset)
+        assert np.array_equal(eo[ok], (e + up).astype(np.uint8)[ok])
+    # the master's stream: decoded values have no mantissa, so the sum of two workers, 2^a + 2^(a-j),
+    # provides one, chosen from the master's word of that element
+    exp = np.zeros((2, d), np.uint8)
+    sgn = np.zeros((2, (d + 7) // 8), np.uint8)
+    rm = np.array([oracle.random_word(seed, 9, 3, index_offset + i) for i in range(d)], np.uint64)
+    top = (rm >> 9).astype(np.int64)
+    # 2^a (1 + 2^-j) has mantissa 2^(23-j): the power of two just below the word's top bits (stays) for
+    # even elements, the one just above (goes up) for odd ones
+    j = np.clip(23 - (np.floor(np.log2(np.maximum(top, 1))).astype(np.int64) + (np.arange(d) & 1)), 1, 23)
+    exp[0] = 120
+    exp[1] = (120 - j).astype(np.uint8)
+    got_e, got_s = nc.master_nat(d, dev(exp), dev(sgn), seed, master=9, index_offset=index_offset)
+    _, eo, so = oracle.master_nat(exp, sgn, d, seed, 9, index_offset)
+    assert np.array_equal(host(got_e), eo) and np.array_equal(host(got_s), so)
+    mant = (1 << (23 - j)).astype(np.int64)
+    want_up = (rm < (mant.astype(np.uint64) << np.uint64(9)))
+    assert np.array_equal(eo.astype(np.int64), 120 + want_up.astype(np.int64))
+    assert want_up.any() and (~want_up).any()
