@@ -95,3 +95,33 @@ def test_empirical_variance_study_on_gpu(nc):
         assert res[p]["nat"]["median"] >= res[p]["sta_exp"]["median"] * 0.98
     big = ev.run(num_vectors=10, d=100_000, s=32, seed=2, ps=("inf",), sta_exp=False)
     assert big["inf"]["sta_same"]["median"] < big["inf"]["nat"]["median"] <= 0.125 * 1.05
+
+
+@pytest.mark.parametrize("s", [4, 8, 128])
+def test_words_at_the_threshold(nc, oracle, s):
+    """Max-norm 1 and s a power of two, so t = y s is exact: y = (j + r / 2^32) / s has threshold r
+    (the element's own word: stays at level j), 512 more units go up.  Only words that are a
+    multiple of 2^9 fit a binary32 fraction for j = 1."""
+    d, seed, worker, off = 4 * 8192, 41, 1, 4
+    r = np.array([oracle.random_word(seed, worker, 1, off + i) for i in range(d)], np.uint64)
+    pick = ((r & np.uint64(511)) == 0) & (r > 0) & (r < (1 << 32) - 512)
+    pick[::512] = False
+    assert pick.sum() > 20
+    rng = np.random.default_rng(3)
+    base = (rng.uniform(0, 1, d)).astype(np.float32)
+    for bump, up in [(0, 0), (512, 1)]:
+        x = base.copy()
+        t = 1.0 + (r[pick] + np.uint64(bump)).astype(np.float64) / 2.0**32
+        x[pick] = (t / s).astype(np.float32)
+        assert np.array_equal(x[pick].astype(np.float64) * s, t)          # exact: nothing was rounded
+        x[::512] = 1.0
+        for bucket in (0, 512):
+            norms, code, sign = nc.dither_encode(dev(x), INF, s, seed, worker, off, bucket=bucket, standard=True)
+            torch.cuda.synchronize()
+            nh = host(norms)
+            assert np.all(nh == 1.0)
+            co, so = oracle.sta_encode(x, s, nh, seed, worker, off, bucket=bucket)
+            assert np.array_equal(host(code), co)
+            idx = np.flatnonzero(pick)
+            c = ((co[idx // 2] >> (4 * (idx & 1))) & (7 if s <= 7 else 15)) if s <= 15 else co[idx]
+            assert np.all(c == 1 + up)
