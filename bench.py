@@ -1,6 +1,6 @@
 """Benchmark of the hot path on one MI355X.
 
-A step is one pass of config 2 (benchmark configs[1]): natural compression of 8 workers'
+A step is one pass of the headline workload ("config 2"): natural compression of 8 workers'
 gradients (d = 25,557,032 fp32 each, 161 layers) in one batched launch, then the fused
 decode-and-sum of the 8 code streams.  Inputs are resident in HBM before the timed region.
 `value` is fp32 input bytes (8 * 4 * d) per second of step time.
