@@ -476,10 +476,11 @@ void dither_bucket_encode_vec_kernel(DitherEncodeArgs a) {
 }
 
 // ------------------------------------------------------------------------ one-pass bucket encoder
+// One bucket by a whole workgroup, lane t owning elements 8t .. 8t+7 of it (BLOCK * 8 >= bucket).
+// All lanes of the workgroup must call; `scratch` has one slot per wavefront.
 template <int BLOCK, int FMT, bool FAST>
-__global__ __launch_bounds__(BLOCK) void dither_bucket_encode_kernel(DitherEncodeArgs a) {
-    __shared__ NormAcc scratch[BLOCK / 64];
-    const uint64_t bucket_index = a.first_bucket + blockIdx.x;
+__device__ __forceinline__ void bucket_encode_by_workgroup(const DitherEncodeArgs& a, uint64_t bucket_index,
+                                                           NormAcc* scratch) {
     const uint64_t begin = bucket_index * a.segs.bucket;
     const uint64_t rest = a.segs.d - begin;
     const uint32_t len = rest < a.segs.bucket ? (uint32_t)rest : a.segs.bucket;
@@ -498,6 +499,11 @@ __global__ __launch_bounds__(BLOCK) void dither_bucket_encode_kernel(DitherEncod
     const float inv[8] = {iv, iv, iv, iv, iv, iv, iv, iv};
     encode_group<FMT, FAST>(a, u, inv, begin + l0, count);
 }
+template <int BLOCK, int FMT, bool FAST>
+__global__ __launch_bounds__(BLOCK) void dither_bucket_encode_kernel(DitherEncodeArgs a) {
+    __shared__ NormAcc scratch[BLOCK / 64];
+    bucket_encode_by_workgroup<BLOCK, FMT, FAST>(a, blockIdx.x, scratch);
+}
 
 // One-pass encoder for power-of-two buckets (32 <= bucket <= 2048), vector path (same
 // alignment as the kernel above).  A workgroup takes a tile of 256 * QPL quads; a bucket of
@@ -507,11 +513,12 @@ __global__ __launch_bounds__(BLOCK) void dither_bucket_encode_kernel(DitherEncod
 // load instruction reads runs of 16 L contiguous bytes and every aligned group of 8 lanes holds
 // 8 consecutive quads (what the packed stores need).  The norm is reduced inside the bucket's
 // lanes with xor-butterfly steps (no LDS, no barrier); the square root and the reciprocal are
-// computed once per lane for its QPL quads.  Only whole buckets are handled (`full_buckets` of
-// them); a ragged last bucket goes to the generic kernel.
+// computed once per lane for its QPL quads.  The tiles hold the `full_buckets` whole buckets; a
+// ragged last bucket is encoded by the last workgroup after its tile, lane by lane.
 template <int QPL, int FMT>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6, 8)))
 void dither_pow2_bucket_encode_kernel(DitherEncodeArgs a, uint32_t log2_l, uint64_t full_buckets) {
+    __shared__ NormAcc scratch[kBlock / 64];
     const uint32_t lanes = 1u << log2_l;                   // L
     const uint32_t b_local = threadIdx.x >> log2_l;        // bucket of this lane inside the tile
     const uint32_t r = threadIdx.x & (lanes - 1u);
@@ -553,6 +560,9 @@ void dither_pow2_bucket_encode_kernel(DitherEncodeArgs a, uint32_t log2_l, uint6
         encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, q_global + q, have);
         __builtin_amdgcn_sched_barrier(0);  // one quad at a time keeps the register count low
     }
+    // the ragged last bucket (fewer than `bucket` <= 2048 elements) is the last workgroup's second job
+    if (blockIdx.x == gridDim.x - 1 && full_buckets * a.segs.bucket < a.segs.d)
+        bucket_encode_by_workgroup<kBlock, FMT, false>(a, full_buckets, scratch);
 }
 
 // Adds to acc the lane's elements that fall into the chunk-local piece [lb, le); the lane
@@ -1143,21 +1153,15 @@ hipError_t launch_dither_bucket_encode(const DitherEncodeArgs& a, bool fast, hip
         uint32_t log2_l = 0;
         while ((qpl << log2_l) < quads) ++log2_l;
         const uint64_t full = a.segs.d / bucket;
-        if (full) {
-            const unsigned tiles = (unsigned)((full * quads + (uint64_t)kBlock * qpl - 1) / ((uint64_t)kBlock * qpl));
-            switch (qpl) {
-                case 1: launch_pow2<1>(a, log2_l, full, tiles, stream); break;
-                case 2: launch_pow2<2>(a, log2_l, full, tiles, stream); break;
-                case 4: launch_pow2<4>(a, log2_l, full, tiles, stream); break;
-                default: launch_pow2<8>(a, log2_l, full, tiles, stream); break;
-            }
-            const hipError_t e = hipGetLastError();
-            if (e != hipSuccess) return e;
+        uint64_t tiles = (full * quads + (uint64_t)kBlock * qpl - 1) / ((uint64_t)kBlock * qpl);
+        if (tiles == 0) tiles = 1;  // a vector shorter than one bucket: only the ragged bucket
+        switch (qpl) {
+            case 1: launch_pow2<1>(a, log2_l, full, (unsigned)tiles, stream); break;
+            case 2: launch_pow2<2>(a, log2_l, full, (unsigned)tiles, stream); break;
+            case 4: launch_pow2<4>(a, log2_l, full, (unsigned)tiles, stream); break;
+            default: launch_pow2<8>(a, log2_l, full, (unsigned)tiles, stream); break;
         }
-        if (full * bucket == a.segs.d) return hipSuccess;
-        DitherEncodeArgs tail = a;  // the ragged last bucket, one workgroup
-        tail.first_bucket = full;
-        return launch_bucket<256, false>(tail, 1, stream);  // 256 lanes x 8 elements cover a bucket of 2048
+        return hipGetLastError();
     }
     if (fast && (a.segs.bucket & 31) == 0) {  // vector path: 256 lanes, QPL quads per lane
         const uint32_t quads = a.segs.bucket / 4;

@@ -55,7 +55,6 @@ struct DitherEncodeArgs {
     double* head_partial;    // one per segment    (two-pass path only)
     float* inv_norm;         // one per segment    (two-pass path only)
     ChunkSegment* chunk_segment;  // one per kChunk elements (two-pass path with segment offsets only)
-    uint64_t first_bucket;        // generic one-pass kernel: index of the bucket workgroup 0 encodes
 };
 struct DitherAggregateArgs {
     const float* norms; size_t norm_stride; const uint8_t* code; size_t code_stride;
