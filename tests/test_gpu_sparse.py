@@ -76,6 +76,20 @@ def test_batch_and_aggregate(nc, oracle, wl, n):
     assert np.all(np.abs(got.astype(np.float64) - o64) <= 1e-5 * oa)
 
 
+@pytest.mark.parametrize("n,d,k", [(3, 8192, 8192), (16, 8191, 4000), (5, 3 * 8192 + 1, 9000), (2, 100_000, 1),
+                                   (33, 20_000, 19_999)])
+def test_sum_with_many_collisions(nc, oracle, wl, n, d, k):
+    """k close to d and magnitudes 1e8 apart between workers: almost every output element receives
+    several workers' entries and the order of the binary32 additions decides the result."""
+    rows = np.stack([wl.dense_gaussian(w, d=d, seed=91) * np.float32(10.0 ** (2 * (w % 5))) for w in range(n)])
+    idx, exp, sign = nc.sparse_nat_encode_batch(dev(rows), k, 1.0, seed=4)
+    o32, _, _ = oracle.sparse_nat_aggregate(host(idx).view(np.uint32), host(exp), host(sign), k, d)
+    out = Guarded(d, torch.float32)
+    nc.sparse_nat_aggregate(idx, exp, sign, k, d, out=out.t)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.check().view(np.uint32), o32.view(np.uint32))
+
+
 def test_unaligned_output_and_tiny_sizes(nc, oracle, wl):
     d, k, n = 1001, 77, 3
     rows = np.stack([wl.dense_gaussian(w, d=d, seed=5) for w in range(n)])
