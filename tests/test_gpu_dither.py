@@ -270,6 +270,22 @@ def test_aggregate_layer_segments_and_odd_strides(nc, oracle, wl):
     assert np.all(np.abs(got.astype(np.float64) - o64) <= 1e-5 * oa)
 
 
+def test_empty_input(nc):
+    """d = 0 is accepted everywhere and touches nothing."""
+    x = torch.empty(0, dtype=torch.float32, device="cuda")
+    for kw in ({}, {"bucket": 512}, {"standard": True}):
+        norms, code, sign = nc.dither_encode(x, 2, 8, 0, **kw)
+        assert code.numel() == 0
+        seg = {k: v for k, v in kw.items() if k == "bucket"}
+        assert nc.dither_decode(norms, code, sign if sign is not None else code, 0, 8,
+                                standard=kw.get("standard", False), **seg).numel() == 0
+    z = torch.empty((3, 0), dtype=torch.uint8, device="cuda")
+    out = torch.full((4,), 5.0, device="cuda")
+    nc.aggregate_sum(nc.NC_KIND_DITHER, 0, z, z, torch.empty((3, 1), dtype=torch.float32, device="cuda"), s=8, out=out)
+    nc.aggregate_sum(nc.NC_KIND_NAT, 0, z, z, out=out)
+    assert torch.all(out == 5.0)
+
+
 def test_workspace_errors(nc):
     x = torch.zeros(10000, dtype=torch.float32, device="cuda")
     need = nc.dither_workspace_bytes(10000, 0, 0, False)
