@@ -73,3 +73,44 @@ def test_argument_errors_without_touching_the_gpu(nc):
     desc.kind, desc.n = nc.NC_KIND_NAT, 0
     assert L.nc_aggregate_sum(ctypes.byref(desc), one, None) == 2
     assert L.nc_status_string(0) == b"NC_OK" and L.nc_status_string(3) == b"NC_ERR_UNSUPPORTED"
+
+
+def test_more_argument_errors_without_touching_the_gpu(nc):
+    """Dithering, clipped-byte, sparse and master entry points: every check below fails (or
+    returns) before any kernel launch."""
+    L = nc.lib()
+    one, inf = ctypes.c_void_p(256), float("inf")
+    # dithering: s outside 1..127 (natural) or 1..255 (standard), an unsupported p, missing pointers, workspace
+    assert L.nc_dither_encode(one, 8, None, 0, 0, 2.0, 0, 0, 0, 0, one, one, one, None, 0, None) == 2
+    assert L.nc_dither_encode(one, 8, None, 0, 0, 2.0, 128, 0, 0, 0, one, one, one, None, 0, None) == 2
+    assert L.nc_dither_sta_encode(one, 8, None, 0, 0, 2.0, 256, 0, 0, 0, one, one, one, None, 0, None) == 2
+    assert L.nc_dither_encode(one, 8, None, 0, 0, 3.0, 8, 0, 0, 0, one, one, one, None, 0, None) == 3
+    assert L.nc_dither_encode(one, 8, None, 0, 0, -inf, 8, 0, 0, 0, one, one, one, None, 0, None) == 3
+    assert L.nc_dither_encode(one, 8, None, 0, 0, 2.0, 8, 0, 0, 0, one, one, None, None, 0, None) == 1   # s = 8 needs a sign plane
+    assert L.nc_dither_encode(one, 8, None, 0, 0, 2.0, 8, 0, 0, 0, one, one, one, None, 0, None) == 4    # whole-vector norm: workspace
+    assert L.nc_dither_encode(one, 8, one, 0, 0, 2.0, 8, 0, 0, 0, one, one, one, one, 1 << 20, None) == 2  # offsets with 0 segments
+    assert L.nc_dither_encode(None, 0, None, 0, 0, 2.0, 8, 0, 0, 0, None, None, None, None, 0, None) == 0
+    # workspace: partial norms per 8192 elements, per-segment slots, and with offsets one record per 2048 elements
+    assert nc.dither_workspace_bytes(10000, 0, 0, False) == 8 * 2 + 8 * 1 + 8
+    assert nc.dither_workspace_bytes(10000, 3, 0, True) == 8 * 2 + 8 * 3 + 16 + 16 * 5
+    assert nc.dither_workspace_bytes(10000, 0, 512, False) == 0 and nc.dither_workspace_bytes(10000, 0, 16384, False) > 0
+    # clipped bytes and the integer sum
+    assert L.nc_nat_clip_encode(None, 0, 1, 8, 0, 0, 0, one, 0, None) == 1
+    assert L.nc_nat_clip_encode(one, 4, 2, 8, 0, 0, 0, one, 8, None) == 2          # x stride below d
+    assert L.nc_nat_clip_encode(None, 0, 0, 8, 0, 0, 0, None, 0, None) == 0        # no workers: nothing to do
+    assert L.nc_nat_clip_decode(None, 8, one, None) == 1
+    assert L.nc_clip_aggregate_int(one, 8, 0, 8, 0, 0, 0, one, one, one, None) == 2
+    assert L.nc_clip_aggregate_int(one, 8, 1, 8, 0, 0, 0, None, None, None, None) == 1   # no output at all
+    assert L.nc_clip_aggregate_int(one, 8, 1, 8, 0, 0, 0, None, one, None, None) == 1    # exponent plane without signs
+    assert L.nc_clip_aggregate_int(one, 4, 2, 8, 0, 0, 0, one, None, None, None) == 2    # stride below d
+    assert L.nc_clip_aggregate_int(one, 8, 1, 8, 0, 0, 0, ctypes.c_void_p(260), None, None, None) == 2  # int64 alignment
+    # sparse messages: k = 0, k > d, d = 0
+    assert L.nc_sparse_nat_encode(one, 8, 0, ctypes.c_float(1.0), 0, 0, one, one, one, None) == 2
+    assert L.nc_sparse_nat_encode(one, 8, 9, ctypes.c_float(1.0), 0, 0, one, one, one, None) == 2
+    assert L.nc_sparse_nat_aggregate(one, 0, one, 0, one, 0, 1, 4, 0, one, None) == 2
+    assert L.nc_sparse_nat_aggregate(one, 0, one, 0, None, 0, 1, 4, 8, one, None) == 1
+    # master compression wants C_nat planes
+    desc = nc.AggDesc()
+    desc.kind, desc.n, desc.d = nc.NC_KIND_DITHER, 1, 8
+    assert L.nc_master_nat(ctypes.byref(desc), 0, 0, 0, one, one, None) == 2
+    assert L.nc_norm_compress(None, 0, 0, 0, None, None, None) == 0 and L.nc_norm_compress(None, 4, 0, 0, one, one, None) == 1
