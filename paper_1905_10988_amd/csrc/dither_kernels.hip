@@ -505,33 +505,36 @@ __global__ __launch_bounds__(BLOCK) void dither_bucket_encode_kernel(DitherEncod
     bucket_encode_by_workgroup<BLOCK, FMT, FAST>(a, blockIdx.x, scratch);
 }
 
-// One-pass encoder for power-of-two buckets (32 <= bucket <= 2048), vector path (same
-// alignment as the kernel above).  A workgroup takes a tile of 256 * QPL quads; a bucket of
-// W = bucket / 4 quads belongs to L = W / QPL consecutive lanes of one wavefront (8 <= L <= 64, a
-// power of two; buckets above 2048 are better served by the one-bucket-per-workgroup kernel
-// above), lane r of them holding quads r, r + L, ..., r + (QPL-1) L of the bucket, so every
-// load instruction reads runs of 16 L contiguous bytes and every aligned group of 8 lanes holds
-// 8 consecutive quads (what the packed stores need).  The norm is reduced inside the bucket's
+// One-pass encoder for buckets of 32 .. 2048 elements that are a multiple of 32, vector path
+// (same alignment as the kernel above).  A workgroup takes 256 / L whole buckets; a bucket of
+// W = bucket / 4 quads belongs to L consecutive lanes of one wavefront (8 <= L <= 64, a power of
+// two with QPL * L >= W; buckets above 2048 are better served by the one-bucket-per-workgroup
+// kernel above), lane r of them holding quads r, r + L, ... of the bucket (those below W), so
+// every load instruction reads runs of up to 16 L contiguous bytes and every aligned group of 8
+// lanes holds 8 consecutive quads (what the packed stores need).  The norm is reduced inside the bucket's
 // lanes with xor-butterfly steps (no LDS, no barrier); the square root and the reciprocal are
 // computed once per lane for its QPL quads.  The tiles hold the `full_buckets` whole buckets; a
 // ragged last bucket is encoded by the last workgroup after its tile, lane by lane.
 template <int QPL, int FMT>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6, 8)))
-void dither_pow2_bucket_encode_kernel(DitherEncodeArgs a, uint32_t log2_l, uint64_t full_buckets) {
+void dither_multi_bucket_encode_kernel(DitherEncodeArgs a, uint32_t log2_l, uint64_t full_buckets) {
     __shared__ NormAcc scratch[kBlock / 64];
     const uint32_t lanes = 1u << log2_l;                   // L
+    const uint32_t quads = a.segs.bucket >> 2;             // W <= QPL * L
     const uint32_t b_local = threadIdx.x >> log2_l;        // bucket of this lane inside the tile
     const uint32_t r = threadIdx.x & (lanes - 1u);
-    const uint32_t q_first = b_local * (lanes * QPL) + r;  // tile-local quad of k = 0
-    const uint64_t tile_quad0 = (uint64_t)blockIdx.x * (kBlock * QPL);
+    const uint32_t q_first = b_local * quads + r;          // tile-local quad of k = 0
+    const uint64_t tile_quad0 = ((uint64_t)blockIdx.x << (8 - log2_l)) * quads;
     const uint64_t bucket_index = ((uint64_t)blockIdx.x << (8 - log2_l)) + b_local;
     const bool have = bucket_index < full_buckets;         // the same for all lanes of a bucket
     const u32x4* __restrict__ xv = reinterpret_cast<const u32x4*>(a.x) + tile_quad0;
     u32x4 v[QPL];
+    bool in[QPL];                                          // W is a multiple of 8: the same for 8 aligned lanes
 #pragma unroll
     for (int k = 0; k < QPL; ++k) {
         v[k] = u32x4{0u, 0u, 0u, 0u};
-        if (have) v[k] = load_stream(xv + q_first + k * lanes);
+        in[k] = have && r + k * lanes < quads;
+        if (in[k]) v[k] = load_stream(xv + q_first + k * lanes);
     }
     NormAcc acc = norm_zero();
     norm_add_quads(acc, v, a.pnorm);
@@ -557,7 +560,7 @@ void dither_pow2_bucket_encode_kernel(DitherEncodeArgs a, uint32_t log2_l, uint6
 #pragma unroll
     for (int k = 0; k < QPL; ++k) {
         const uint32_t q = q_first + k * lanes;
-        encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, q_global + q, have);
+        encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, q_global + q, in[k]);
         __builtin_amdgcn_sched_barrier(0);  // one quad at a time keeps the register count low
     }
     // the ragged last bucket (fewer than `bucket` <= 2048 elements) is the last workgroup's second job
@@ -1134,32 +1137,35 @@ static hipError_t launch_bucket_vec(const DitherEncodeArgs& a, unsigned grid, hi
 }
 
 template <int QPL>
-static void launch_pow2(const DitherEncodeArgs& a, uint32_t log2_l, uint64_t full, unsigned tiles, hipStream_t st) {
+static void launch_multi(const DitherEncodeArgs& a, uint32_t log2_l, uint64_t full, unsigned tiles, hipStream_t st) {
     switch (a.fmt) {
-        case kFmtFused: dither_pow2_bucket_encode_kernel<QPL, kFmtFused><<<tiles, kBlock, 0, st>>>(a, log2_l, full); break;
-        case kFmtNibble: dither_pow2_bucket_encode_kernel<QPL, kFmtNibble><<<tiles, kBlock, 0, st>>>(a, log2_l, full); break;
-        default: dither_pow2_bucket_encode_kernel<QPL, kFmtByte><<<tiles, kBlock, 0, st>>>(a, log2_l, full); break;
+        case kFmtFused: dither_multi_bucket_encode_kernel<QPL, kFmtFused><<<tiles, kBlock, 0, st>>>(a, log2_l, full); break;
+        case kFmtNibble: dither_multi_bucket_encode_kernel<QPL, kFmtNibble><<<tiles, kBlock, 0, st>>>(a, log2_l, full); break;
+        default: dither_multi_bucket_encode_kernel<QPL, kFmtByte><<<tiles, kBlock, 0, st>>>(a, log2_l, full); break;
     }
 }
 
 hipError_t launch_dither_bucket_encode(const DitherEncodeArgs& a, bool fast, hipStream_t stream) {
     const unsigned grid = (unsigned)((a.segs.d + a.segs.bucket - 1) / a.segs.bucket);
     const uint32_t bucket = a.segs.bucket;
-    if (fast && bucket >= 32 && bucket <= 2048 && (bucket & (bucket - 1)) == 0) {
-        // power-of-two buckets: QPL quads per lane, L = bucket / 4 / QPL lanes per bucket (>= 8)
+    if (fast && bucket >= 32 && bucket <= 2048 && (bucket & 31) == 0) {
+        // QPL quads per lane, L lanes per bucket with QPL * L = the power of two at or above bucket / 4
         const uint32_t quads = bucket / 4;
+        uint32_t pow2 = 8;
+        while (pow2 < quads) pow2 <<= 1;
         // measured best: runs of at least 256 contiguous bytes per load where the bucket allows it
-        const int qpl = quads <= 8 ? 1 : quads <= 32 ? 2 : quads <= 128 ? 4 : 8;
+        const int qpl = pow2 <= 8 ? 1 : pow2 <= 32 ? 2 : pow2 <= 128 ? 4 : 8;
         uint32_t log2_l = 0;
-        while ((qpl << log2_l) < quads) ++log2_l;
+        while (((uint32_t)qpl << log2_l) < pow2) ++log2_l;
         const uint64_t full = a.segs.d / bucket;
-        uint64_t tiles = (full * quads + (uint64_t)kBlock * qpl - 1) / ((uint64_t)kBlock * qpl);
+        const uint64_t per_tile = (uint64_t)kBlock >> log2_l;  // buckets per workgroup
+        uint64_t tiles = (full + per_tile - 1) / per_tile;
         if (tiles == 0) tiles = 1;  // a vector shorter than one bucket: only the ragged bucket
         switch (qpl) {
-            case 1: launch_pow2<1>(a, log2_l, full, (unsigned)tiles, stream); break;
-            case 2: launch_pow2<2>(a, log2_l, full, (unsigned)tiles, stream); break;
-            case 4: launch_pow2<4>(a, log2_l, full, (unsigned)tiles, stream); break;
-            default: launch_pow2<8>(a, log2_l, full, (unsigned)tiles, stream); break;
+            case 1: launch_multi<1>(a, log2_l, full, (unsigned)tiles, stream); break;
+            case 2: launch_multi<2>(a, log2_l, full, (unsigned)tiles, stream); break;
+            case 4: launch_multi<4>(a, log2_l, full, (unsigned)tiles, stream); break;
+            default: launch_multi<8>(a, log2_l, full, (unsigned)tiles, stream); break;
         }
         return hipGetLastError();
     }

@@ -103,9 +103,9 @@ def test_layer_segments(nc, oracle, wl):
     roundtrip(nc, oracle, x, 2, 8, offsets=np.array([0, d], np.uint64))
 
 
-@pytest.mark.parametrize("bucket", [32, 64, 128, 256, 512, 1024, 2048, 4096, 8192])
-def test_power_of_two_buckets(nc, oracle, wl, bucket):
-    """The kernel that gives a bucket to 8..256 lanes of a workgroup: whole tiles, a partial
+@pytest.mark.parametrize("bucket", [32, 64, 96, 128, 160, 256, 480, 512, 992, 1024, 1536, 2016, 2048, 4096, 8192])
+def test_buckets_sharing_a_workgroup(nc, oracle, wl, bucket):
+    """The kernel that gives a bucket (a multiple of 32) to 8..64 lanes of a workgroup: whole tiles, a partial
     last tile, a ragged last bucket (also one that is not a multiple of 8), a vector shorter
     than one bucket; all three code formats and norms; a non-zero index offset."""
     for d in (4 * max(bucket, 2048), 2048 + 3 * bucket, 5 * 2048 + bucket + 40, 7 * bucket + 13, bucket - 5):
