@@ -856,6 +856,27 @@ __device__ __forceinline__ void dither_sum_chunk(const DitherAggregateArgs& a, c
     dither_add_codes<FMT, NW>(rows, row_stride, w_table, cw, sb, acc);
 }
 
+// NW workers of the lane's group decoded arithmetically with the norms of segment seg.
+template <int FMT, int NW>
+__device__ __forceinline__ void dither_sum_chunk_arith(const DitherAggregateArgs& a, uint64_t grp, size_t w0,
+                                                       uint32_t seg, float acc[8]) {
+    uint32_t cw[NW], sb[NW];
+    float norm[NW];
+    dither_load_codes<FMT, NW>(a, grp, w0, cw, sb);
+#pragma unroll
+    for (int k = 0; k < NW; ++k) norm[k] = a.norms[(w0 + k) * a.norm_stride + seg];
+#pragma unroll
+    for (int k = 0; k < NW; ++k) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t nib = (cw[k] >> (4 * j)) & 15u;
+            const uint32_t c = (FMT == kFmtFused) ? (nib & 7u) : nib;
+            const uint32_t sgn = (FMT == kFmtFused) ? (nib >> 3) : ((sb[k] >> j) & 1u);
+            acc[j] += dither_value(norm[k], a.s, c, sgn, a.standard);
+        }
+    }
+}
+
 // One element of the sum by plain arithmetic (any layout and alignment).
 template <int FMT>
 __device__ __forceinline__ float dither_sum_one(const DitherAggregateArgs& a, uint64_t i, uint32_t seg) {
@@ -909,6 +930,7 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
         else if (n_first == 1) dither_load_codes<FMT, 1>(a, grp, 0, cw0, sb0);
     }
     uint32_t s0, log2_nbk = 0, lane_bucket = 0, nseg = 0;
+    uint64_t s0_begin = 0;
     bool one_segment;
     if (kMulti) {  // the chunk holds 2^log2_nbk whole buckets, the first of index s0
         log2_nbk = 11u - a.log2_bucket;  // kChunk = 2^11
@@ -919,6 +941,7 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
     } else {
         const SegHit hit = seg_find_block(sg, cb, nullptr, &slot);
         s0 = hit.s;
+        s0_begin = hit.begin;
         one_segment = hit.end >= ce;
     }
     const uint32_t nbk = 1u << log2_nbk;
@@ -959,6 +982,18 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
 #pragma unroll
             for (int j = 0; j < 8; ++j)
                 if ((uint32_t)j < count) acc[j] = dither_sum_one<FMT>(a, i0 + j, s0 + lane_bucket);
+        }
+    } else if (kTables && !sg.offsets && (sg.bucket & 7u) == 0 && sg.bucket <= (1u << 20)) {
+        // buckets that are a multiple of 8 (not a power of two, or too small for tables): the lane's 8
+        // elements share one bucket, whose index follows from the position; codes still come as words
+        const uint32_t seg = s0 + ((uint32_t)(cb - s0_begin) + threadIdx.x * 8u) / sg.bucket;
+        if (count == 8) {
+            uint32_t w = 0;
+            for (; w + 4 <= a.n; w += 4) dither_sum_chunk_arith<FMT, 4>(a, grp, w, seg, acc);
+            for (; w < a.n; ++w) dither_sum_chunk_arith<FMT, 1>(a, grp, w, seg, acc);
+        } else if (count) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) if ((uint32_t)j < count) acc[j] = dither_sum_one<FMT>(a, i0 + j, seg);
         }
     } else {
         const uint32_t nb = one_segment ? 0u : stage_boundaries(sg, cb, ce, s0, bnd);  // block-uniform
