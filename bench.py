@@ -245,6 +245,13 @@ def main():
     enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
     agg_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
 
+    # reference: a plain device-to-device copy of 1 GiB (bytes read + bytes written per second)
+    src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    copy_ms = _time_ms(torch, np, lambda: dst.copy_(src), reps=10)
+    copy_gbs = 2.0 * src.numel() * 4 / (copy_ms * 1e-3) / 1e9
+    del src, dst
+
     input_bytes = 4.0 * d * n
     value = input_bytes / (ms_per_step * 1e-3) / 1e9
     enc_alg = ENCODE_BYTES_PER_ELEM * d * n
@@ -280,6 +287,8 @@ def main():
             "traffic": measured_traffic("nat_encode_config2_pmc.txt"),
             "algorithmic_bytes_per_launch": enc_alg,
             "avg_launch_ms": round(enc_ms, 5),
+            "device_copy_GBps": round(copy_gbs, 1),
+            "frac_of_device_copy": round(enc_gbs / copy_gbs, 4),
         },
         "roofline_aggregate": {
             "kernel": "nat_aggregate_kernel (n=8)",
@@ -291,6 +300,7 @@ def main():
             "traffic": measured_traffic("nat_aggregate_config2_pmc.txt"),
             "algorithmic_bytes_per_launch": agg_alg,
             "avg_launch_ms": round(agg_ms, 5),
+            "frac_of_device_copy": round(agg_gbs / copy_gbs, 4),
         },
     }
 
