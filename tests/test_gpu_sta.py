@@ -65,17 +65,25 @@ def test_segments_sizes_offsets(nc, oracle, wl):
     roundtrip(nc, oracle, np.zeros(64, np.float32), 2, 4)
 
 
-def test_aggregate_standard(nc, oracle, wl):
-    d, bucket, n, s = 3 * 8192 + 77, 8192, 8, 4
+@pytest.mark.parametrize("bucket,n,s", [(8192, 8, 4), (512, 8, 4), (64, 3, 8), (96, 5, 8), (1000, 2, 4), (2048, 17, 15),
+                                        (256, 4, 200), (0, 3, 7)])
+def test_aggregate_standard(nc, oracle, wl, bucket, n, s):
+    """One table per worker (buckets of 8192), one per (worker, bucket) for small powers of two, the
+    arithmetic paths for other sizes and for byte codes; whole vector as one segment."""
+    d = 3 * 8192 + 77
     nseg = nc.segment_count(d, 0, bucket, False)
+    nsign = nc.dither_sign_bytes(d, s)
     norms = torch.zeros((n, nseg), dtype=torch.float32, device="cuda")
     code = torch.zeros((n, nc.plane_stride(nc.dither_code_bytes(d, s))), dtype=torch.uint8, device="cuda")
+    sign = torch.zeros((n, nc.plane_stride(max(nsign, 1))), dtype=torch.uint8, device="cuda")
     dec = []
     for w in range(n):
-        x = wl.bucketed_gaussian(w, d=d, bucket=bucket, seed=31)
-        nc.dither_encode(dev(x), INF, s, 9, worker=w, bucket=bucket, norms_out=norms[w], code_out=code[w], standard=True)
-        dec.append(oracle.sta_decode(host(norms[w]), host(code[w]), None, d, s, bucket=bucket))
-    got = host(nc.aggregate_sum(nc.NC_KIND_DITHER_STA, d, code, None, norms, s=s, bucket=bucket))
+        x = wl.bucketed_gaussian(w, d=d, bucket=max(bucket, 64), seed=31)
+        nc.dither_encode(dev(x), INF, s, 9, worker=w, bucket=bucket, norms_out=norms[w], code_out=code[w],
+                         sign_out=sign[w] if nsign else None, standard=True)
+        dec.append(oracle.sta_decode(host(norms[w]), host(code[w]), host(sign[w]) if nsign else None, d, s,
+                                     bucket=bucket))
+    got = host(nc.aggregate_sum(nc.NC_KIND_DITHER_STA, d, code, sign if nsign else None, norms, s=s, bucket=bucket))
     seq = dec[0].copy()
     for w in range(1, n):
         seq = (seq + dec[w]).astype(np.float32)
