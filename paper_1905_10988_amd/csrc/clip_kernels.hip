@@ -122,10 +122,11 @@ __device__ __forceinline__ uint64_t clip_units(uint32_t byte) {
 // bits, sign-extended to 64 bits) shifted left by the field; a two's complement shift of -1
 // gives -2^field.
 __device__ __forceinline__ uint64_t clip_units_at(uint32_t word, int j) {
-    const int32_t neg = (int32_t)(word << (24 - 8 * j)) >> 31;  // 0 or -1
-    const int32_t zer = (int32_t)(word << (25 - 8 * j)) >> 31;
-    const int64_t unit = (int64_t)((neg | 1) & ~zer);
-    return (uint64_t)unit << ((word >> (8 * j)) & 63u);
+    const uint32_t neg = (uint32_t)__builtin_amdgcn_sbfe((int32_t)word, 8 * j + 7, 1);  // 0 or all ones
+    const uint32_t zer = (uint32_t)__builtin_amdgcn_sbfe((int32_t)word, 8 * j + 6, 1);
+    const uint32_t lo = __builtin_amdgcn_bitop3_b32(neg, 1u, zer, 0x54);  // (neg | 1) & ~zer
+    const uint32_t hi = __builtin_amdgcn_bitop3_b32(neg, 0u, zer, 0x50);  // neg & ~zer: the sign extension
+    return (((uint64_t)hi << 32) | lo) << ((word >> (8 * j)) & 63u);
 }
 
 // C_nat of the integer sum: exponent field of the result (0 for a zero sum).  With
