@@ -989,7 +989,7 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
         const uint32_t seg = s0 + ((uint32_t)(cb - s0_begin) + threadIdx.x * 8u) / sg.bucket;
         if (count == 8) {
             uint32_t w = 0;
-            for (; w + 4 <= a.n; w += 4) dither_sum_chunk_arith<FMT, 4>(a, grp, w, seg, acc);
+            for (; w + 2 <= a.n; w += 2) dither_sum_chunk_arith<FMT, 2>(a, grp, w, seg, acc);  // (4 at a time would cost the table path its occupancy)
             for (; w < a.n; ++w) dither_sum_chunk_arith<FMT, 1>(a, grp, w, seg, acc);
         } else if (count) {
 #pragma unroll
