@@ -77,10 +77,7 @@ __device__ __forceinline__ uint64_t seg_end(const Segs& sg, uint32_t s) {
     const uint64_t e = ((uint64_t)s + 1) * sg.bucket;
     return e < sg.d ? e : sg.d;
 }
-__device__ __forceinline__ uint32_t seg_count(const Segs& sg) {
-    if (sg.offsets) return sg.num_segments;
-    return sg.bucket ? (uint32_t)((sg.d + sg.bucket - 1) / sg.bucket) : 1u;
-}
+__device__ __forceinline__ uint32_t seg_count(const Segs& sg) { return sg.count; }
 
 // Segment boundaries inside one chunk, staged in LDS.  Segment s0 holds the chunk's first
 // element cb; lane t looks at the begin of segment s0 + 1 + t and, if it lies before the
@@ -936,7 +933,7 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
         log2_nbk = 11u - a.log2_bucket;  // kChunk = 2^11
         s0 = blockIdx.x << log2_nbk;
         lane_bucket = (threadIdx.x * 8u) >> a.log2_bucket;
-        nseg = (uint32_t)((sg.d + sg.bucket - 1) >> a.log2_bucket);
+        nseg = seg_count(sg);
         one_segment = true;  // (for the table path: every lane's elements have a table)
     } else {
         const SegHit hit = seg_find_block(sg, cb, nullptr, &slot);

@@ -29,6 +29,7 @@ struct NatAggregateArgs {
 // ascending values), or a fixed bucket length, or (both absent) one segment.
 struct Segs {
     const uint64_t* offsets; uint32_t num_segments; uint32_t bucket; uint64_t d;
+    uint32_t count;   // number of segments whichever way they are described (set by the host)
 };
 
 enum { kNormL1 = 1, kNormL2 = 2, kNormInf = 3 };

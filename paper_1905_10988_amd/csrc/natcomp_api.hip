@@ -97,6 +97,7 @@ static nc_status check_segments(uint64_t d, const uint64_t* seg_offsets, uint32_
     out->num_segments = seg_offsets ? num_segments : 0;
     out->bucket = seg_offsets ? 0 : bucket;
     out->d = d;
+    out->count = (uint32_t)nc_segment_count(d, num_segments, bucket, seg_offsets != nullptr);
     return NC_OK;
 }
 static inline bool one_pass_bucket(const uint64_t* seg_offsets, uint32_t bucket) {
