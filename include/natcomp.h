@@ -30,6 +30,11 @@
  *                     b == 4: nibble plane of codes (same order) + sign plane;
  *                     b >= 5: one byte per code + sign plane.
  *                   Planes are indexed by the element's position in the call's vector.
+ *
+ * Sizes: a call takes at most d = 2^34 elements (NC_ERR_INVALID beyond: one launch holds fewer
+ * than 2^32 lanes); the sparse entry points take d <= 2^32 (32-bit indices).  A launch the
+ * device rejects (for example one workgroup per bucket with hundreds of millions of tiny
+ * buckets) is reported as NC_ERR_LAUNCH; nothing has run in that case.
  */
 #ifndef NATCOMP_H
 #define NATCOMP_H

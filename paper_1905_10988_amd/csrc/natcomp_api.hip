@@ -11,7 +11,8 @@ using namespace natcomp;
 
 namespace {
 
-constexpr uint64_t kMaxD = 1ull << 40;  // keeps every grid dimension below 2^31
+// A launch may hold at most 2^32 - 1 lanes; the vector kernels give a lane 4 to 32 elements.
+constexpr uint64_t kMaxD = 1ull << 34;
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 inline nc_status from_hip(hipError_t e) { return e == hipSuccess ? NC_OK : NC_ERR_LAUNCH; }
