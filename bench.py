@@ -320,11 +320,21 @@ def main():
             oracle.aggregate_nat(exp_h, sign_h, d)
             reps += 1
         dt = (time.perf_counter() - t0) / reps
+        # the same oracle on one core: one worker's encode and a one-stream decode
+        cores = oracle.threads()
+        oracle.set_threads(1)
+        t1 = time.perf_counter()
+        e1, s1 = oracle.nat_encode(x_host[0], 1000, 0)
+        oracle.nat_decode(e1, s1, d)
+        dt1 = time.perf_counter() - t1
+        oracle.set_threads(cores)
         result["cpu_baseline"] = {
             "value": round(n * 4.0 * d / dt / 1e9, 3),
             "unit": "GB/s",
-            "cores": oracle.threads(),
+            "cores": cores,
             "kind": "oracle",
+            "single_core_value": round(4.0 * d / dt1 / 1e9, 3),
+            "single_core_sample": f"one worker (d={d}) encoded and decoded on one thread, {dt1:.2f} s",
             "sample": f"{reps} whole steps (8 workers x d={d} encoded, 8 streams decoded+summed each), "
                       f"{dt:.2f} s of wall time per step",
         }

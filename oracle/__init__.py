@@ -112,6 +112,11 @@ def threads():
     return int(lib().orc_threads())
 
 
+def set_threads(n):
+    """Sets the number of OpenMP threads of the element-parallel loops (timing only: results do not depend on it)."""
+    lib().orc_set_threads(int(n))
+
+
 def _ptr(a, typ):
     return None if a is None else a.ctypes.data_as(typ)
 

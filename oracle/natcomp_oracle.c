@@ -441,8 +441,10 @@ void orc_aggregate_dither(const float *norms, uint64_t norm_stride, const uint8_
 #ifdef _OPENMP
 #include <omp.h>
 int orc_threads(void) { return omp_get_max_threads(); }
+void orc_set_threads(int n) { if (n > 0) omp_set_num_threads(n); }
 #else
 int orc_threads(void) { return 1; }
+void orc_set_threads(int n) { (void)n; }
 #endif
 
 /* ------------------------------------------------------------------------ */
