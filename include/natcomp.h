@@ -160,6 +160,16 @@ nc_status nc_dither_sta_decode(const float *norms, const uint8_t *code, const ui
 nc_status nc_norm_compress(const float *norms, uint64_t count, uint64_t seed, uint32_t worker,
                            uint8_t *exp_out, float *norms_q_out, void *stream);
 
+/* Decoding straight from the 8-bit norms: norm_exp[s] is the exponent byte nc_norm_compress
+ * wrote (the norm 2^(e-127), e = 0 meaning 0), so the wire carries one byte per norm and the
+ * product norm * 2^(c-s) is the exponent sum e + c - s (Sec. 3 and the appendix on fast
+ * aggregation).  Same result, bit for bit, as nc_dither_decode with the power-of-two floats.
+ * For the sum over workers use nc_aggregate_sum with kind = NC_KIND_DITHER_NORM8: `norms`
+ * then points at the exponent bytes (cast to const float *) and norm_stride counts bytes. */
+nc_status nc_dither_decode_norm8(const uint8_t *norm_exp, const uint8_t *code, const uint8_t *sign, uint64_t d,
+                                 const uint64_t *seg_offsets, uint32_t num_segments, uint32_t bucket,
+                                 uint32_t s, float *out, void *stream);
+
 /* ----------------------------------------------------------------------------------------
  * Master-side aggregation (Algorithm 1: Delta = sum over workers of the decompressed
  * updates).  One fused kernel decodes the n code streams and adds them in binary32 in the
@@ -171,9 +181,10 @@ nc_status nc_norm_compress(const float *norms, uint64_t count, uint64_t seed, ui
  *   kind = NC_KIND_DITHER: code/sign/norms as written by nc_dither_encode with the same s and
  *                          segment description; sign may be NULL when s <= 7.
  *   kind = NC_KIND_DITHER_STA: the same for nc_dither_sta_encode.
+ *   kind = NC_KIND_DITHER_NORM8: as NC_KIND_DITHER with 8-bit norms (see nc_dither_decode_norm8).
  * out: DEVICE, d floats.  Fastest when strides are multiples of 16 and planes 16-byte aligned.
  * -------------------------------------------------------------------------------------- */
-enum { NC_KIND_NAT = 0, NC_KIND_DITHER = 1, NC_KIND_DITHER_STA = 2 };
+enum { NC_KIND_NAT = 0, NC_KIND_DITHER = 1, NC_KIND_DITHER_STA = 2, NC_KIND_DITHER_NORM8 = 3 };
 
 typedef struct {
     int32_t kind;

@@ -810,6 +810,15 @@ __global__ __launch_bounds__(kBlock) void dither_segment_encode_kernel(DitherEnc
 }
 
 // ------------------------------------------------------------------------ decode and sum
+// Norm of (worker row, segment): a binary32 value, or (norm8) the exponent byte of a norm that
+// natural compression rounded to a power of two, 2^(e-127) with e = 0 standing for 0.  Times a
+// level 2^(c-s) that is the exponent sum e + c - s; the decoders keep the one multiply, which
+// costs the same as an integer add and also covers results below the normal range.
+__device__ __forceinline__ float load_norm(const DitherAggregateArgs& a, size_t index) {
+    if (a.norm8) return bits_f32((uint32_t)reinterpret_cast<const uint8_t*>(a.norms)[index] << 23);
+    return a.norms[index];
+}
+
 // Value bits of (norm, code c, sign): sign | fl(norm * 2^(c-s)), a signed zero for c = 0.
 __device__ __forceinline__ float dither_value(float norm, uint32_t s, uint32_t c, uint32_t sign_bit,
                                               uint32_t standard) {
@@ -861,7 +870,7 @@ __device__ __forceinline__ void dither_sum_chunk_arith(const DitherAggregateArgs
     float norm[NW];
     dither_load_codes<FMT, NW>(a, grp, w0, cw, sb);
 #pragma unroll
-    for (int k = 0; k < NW; ++k) norm[k] = a.norms[(w0 + k) * a.norm_stride + seg];
+    for (int k = 0; k < NW; ++k) norm[k] = load_norm(a, (w0 + k) * a.norm_stride + seg);
 #pragma unroll
     for (int k = 0; k < NW; ++k) {
 #pragma unroll
@@ -889,7 +898,7 @@ __device__ __forceinline__ float dither_sum_one(const DitherAggregateArgs& a, ui
             if (FMT == kFmtFused) { c = nib & 7u; sgn = nib >> 3; }
             else { c = nib; sgn = (a.sign[(size_t)w * a.sign_stride + (i >> 3)] >> (i & 7)) & 1u; }
         }
-        acc += dither_value(a.norms[(size_t)w * a.norm_stride + seg], a.s, c, sgn, a.standard);
+        acc += dither_value(load_norm(a, (size_t)w * a.norm_stride + seg), a.s, c, sgn, a.standard);
     }
     return acc;
 }
@@ -953,7 +962,7 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
             // tabulate: entry ((worker, bucket), nibble)
             for (uint32_t e = threadIdx.x; e < (nw << (4u + log2_nbk)); e += kBlock) {
                 const uint32_t w = e >> (4u + log2_nbk), seg = s0 + ((e >> 4) & (nbk - 1u)), nib = e & 15u;
-                const float norm = (!kMulti || seg < nseg) ? a.norms[(size_t)(w0 + w) * a.norm_stride + seg] : 0.0f;
+                const float norm = (!kMulti || seg < nseg) ? load_norm(a, (size_t)(w0 + w) * a.norm_stride + seg) : 0.0f;
                 table[e] = (FMT == kFmtFused) ? dither_value(norm, a.s, nib & 7u, nib >> 3, a.standard)
                                               : dither_value(norm, a.s, nib, 0u, a.standard);
             }
@@ -1057,13 +1066,13 @@ __global__ __launch_bounds__(kBlock) void dither_decode_kernel(DitherAggregateAr
         cw = load_stream(code_base + grp_local);
         if (FMT == kFmtNibble) sb = load_stream(sign_base + grp_local);
     }
-    const SegHit hit = seg_find_block(sg, cb, a.norms, &slot);
+    const SegHit hit = seg_find_block(sg, cb, a.norm8 ? nullptr : a.norms, &slot);
     const uint32_t s0 = hit.s;
     const bool one_segment = hit.end >= ce;
     uint32_t bits[8];
     if (one_segment) {
         if (threadIdx.x < 16) {
-            const float norm = hit.aux;
+            const float norm = a.norm8 ? load_norm(a, s0) : hit.aux;
             table[threadIdx.x] = (FMT == kFmtFused)
                                      ? dither_value(norm, a.s, threadIdx.x & 7u, threadIdx.x >> 3, a.standard)
                                      : dither_value(norm, a.s, threadIdx.x, 0u, a.standard);
@@ -1080,7 +1089,7 @@ __global__ __launch_bounds__(kBlock) void dither_decode_kernel(DitherAggregateAr
         // buckets that are a multiple of 8: the lane's 8 elements share one bucket, whose index
         // follows from the position alone (no search, so the norm load is not behind a barrier)
         const uint32_t seg = s0 + ((uint32_t)(cb - hit.begin) + l0) / sg.bucket;
-        const float norm = a.norms[seg < seg_count(sg) ? seg : s0];  // (lanes past the end: any valid index)
+        const float norm = load_norm(a, seg < seg_count(sg) ? seg : s0);  // (lanes past the end: any valid index)
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const uint32_t nib = (cw >> (4 * j)) & 15u;
@@ -1093,16 +1102,16 @@ __global__ __launch_bounds__(kBlock) void dither_decode_kernel(DitherAggregateAr
         SegCursor cur;
         if (nb < (uint32_t)kBlock) cur = cursor_at(bnd, nb, l0);
         else cur = SegCursor{count ? seg_find(sg, cb + l0) - s0 : 0u, 0u};
-        float norm = a.norms[s0 + cur.idx];
+        float norm = load_norm(a, s0 + cur.idx);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             if (nb < (uint32_t)kBlock) {
-                if (cursor_advance(cur, bnd, nb, l0 + j)) norm = a.norms[s0 + cur.idx];
+                if (cursor_advance(cur, bnd, nb, l0 + j)) norm = load_norm(a, s0 + cur.idx);
             } else if (count) {
                 const uint32_t last = seg_count(sg) - 1;
                 while (cb + l0 + j >= seg_end(sg, s0 + cur.idx) && s0 + cur.idx < last) {
                     ++cur.idx;
-                    norm = a.norms[s0 + cur.idx];
+                    norm = load_norm(a, s0 + cur.idx);
                 }
             }
             const uint32_t nib = (cw >> (4 * j)) & 15u;

@@ -62,6 +62,7 @@ struct DitherAggregateArgs {
     const uint8_t* sign; size_t sign_stride;
     uint32_t n; Segs segs; uint32_t s; int fmt; uint32_t standard; float* out;
     uint32_t log2_bucket;   // set by the launcher for the kernel with per-bucket tables
+    uint32_t norm8;         // 1: `norms` points at exponent bytes (norms rounded to powers of two)
 };
 
 // One-pass encoder for fixed buckets of at most kMaxOnePassBucket elements (a multiple of 8).

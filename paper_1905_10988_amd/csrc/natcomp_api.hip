@@ -172,7 +172,7 @@ nc_status nc_dither_sta_encode(const float* x, uint64_t d, const uint64_t* seg_o
                          code_out, sign_out, workspace, workspace_bytes, stream);
 }
 
-static nc_status dither_aggregate(uint32_t standard, const float* norms, size_t norm_stride, const uint8_t* code, size_t code_stride,
+static nc_status dither_aggregate(uint32_t standard, uint32_t norm8, const float* norms, size_t norm_stride, const uint8_t* code, size_t code_stride,
                                   const uint8_t* sign, size_t sign_stride, uint32_t n, uint64_t d,
                                   const uint64_t* seg_offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
                                   float* out, void* stream) {
@@ -191,6 +191,7 @@ static nc_status dither_aggregate(uint32_t standard, const float* norms, size_t 
     }
     a.norms = norms; a.norm_stride = norm_stride; a.code = code; a.code_stride = code_stride;
     a.sign = sign; a.sign_stride = sign_stride; a.n = n; a.s = s; a.fmt = fmt; a.standard = standard; a.out = out;
+    a.norm8 = norm8;
     const bool fast = aligned(code, 4) && aligned(out, 16) && (n == 1 || (code_stride & 3) == 0);
     return from_hip(launch_dither_aggregate(a, fast, (hipStream_t)stream));
 }
@@ -198,13 +199,20 @@ static nc_status dither_aggregate(uint32_t standard, const float* norms, size_t 
 nc_status nc_dither_decode(const float* norms, const uint8_t* code, const uint8_t* sign, uint64_t d,
                            const uint64_t* seg_offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
                            float* out, void* stream) {
-    return dither_aggregate(0, norms, 0, code, 0, sign, 0, 1, d, seg_offsets, num_segments, bucket, s, out, stream);
+    return dither_aggregate(0, 0, norms, 0, code, 0, sign, 0, 1, d, seg_offsets, num_segments, bucket, s, out, stream);
+}
+
+nc_status nc_dither_decode_norm8(const uint8_t* norm_exp, const uint8_t* code, const uint8_t* sign, uint64_t d,
+                                 const uint64_t* seg_offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
+                                 float* out, void* stream) {
+    return dither_aggregate(0, 1, reinterpret_cast<const float*>(norm_exp), 0, code, 0, sign, 0, 1, d, seg_offsets,
+                            num_segments, bucket, s, out, stream);
 }
 
 nc_status nc_dither_sta_decode(const float* norms, const uint8_t* code, const uint8_t* sign, uint64_t d,
                                const uint64_t* seg_offsets, uint32_t num_segments, uint32_t bucket, uint32_t s,
                                float* out, void* stream) {
-    return dither_aggregate(1, norms, 0, code, 0, sign, 0, 1, d, seg_offsets, num_segments, bucket, s, out, stream);
+    return dither_aggregate(1, 0, norms, 0, code, 0, sign, 0, 1, d, seg_offsets, num_segments, bucket, s, out, stream);
 }
 
 nc_status nc_sparse_nat_encode_batch(const float* x, size_t x_stride, uint32_t n, uint64_t d, uint64_t k, float scale,
@@ -303,7 +311,9 @@ nc_status nc_clip_aggregate_int(const uint8_t* code, size_t code_stride, uint32_
 nc_status nc_aggregate_sum(const nc_agg_desc* desc, float* out, void* stream) {
     if (!desc) return NC_ERR_NULL;
     if (desc->n == 0 || desc->d > kMaxD) return NC_ERR_INVALID;
-    if (desc->kind != NC_KIND_NAT && desc->kind != NC_KIND_DITHER && desc->kind != NC_KIND_DITHER_STA) return NC_ERR_INVALID;
+    if (desc->kind != NC_KIND_NAT && desc->kind != NC_KIND_DITHER && desc->kind != NC_KIND_DITHER_STA &&
+        desc->kind != NC_KIND_DITHER_NORM8)
+        return NC_ERR_INVALID;
     if (desc->d == 0) return NC_OK;
     if (!out || !desc->code) return NC_ERR_NULL;
     if (desc->kind == NC_KIND_NAT) {
@@ -314,7 +324,7 @@ nc_status nc_aggregate_sum(const nc_agg_desc* desc, float* out, void* stream) {
         const bool fast = aligned(desc->code, 8) && aligned(out, 16) && (desc->n == 1 || (desc->code_stride & 7) == 0);
         return from_hip(launch_nat_aggregate(a, fast, (hipStream_t)stream));
     }
-    return dither_aggregate(desc->kind == NC_KIND_DITHER_STA ? 1u : 0u, desc->norms, desc->norm_stride, desc->code, desc->code_stride, desc->sign,
+    return dither_aggregate(desc->kind == NC_KIND_DITHER_STA ? 1u : 0u, desc->kind == NC_KIND_DITHER_NORM8 ? 1u : 0u, desc->norms, desc->norm_stride, desc->code, desc->code_stride, desc->sign,
                             desc->sign_stride, desc->n, desc->d, desc->seg_offsets, desc->num_segments, desc->bucket,
                             desc->s, out, stream);
 }

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libnatcomp.so")
 NC_KIND_NAT = 0
 NC_KIND_DITHER = 1
 NC_KIND_DITHER_STA = 2
+NC_KIND_DITHER_NORM8 = 3
 
 _vp, _u32, _u64, _sz = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_size_t
 
@@ -67,6 +68,8 @@ def lib():
         L.nc_dither_decode.argtypes = [_vp, _vp, _vp, _u64, _vp, _u32, _u32, _u32, _vp, _vp]
         L.nc_dither_sta_encode.argtypes = L.nc_dither_encode.argtypes
         L.nc_dither_sta_decode.argtypes = L.nc_dither_decode.argtypes
+        L.nc_dither_decode_norm8.argtypes = L.nc_dither_decode.argtypes
+        L.nc_dither_decode_norm8.restype = ctypes.c_int
         L.nc_dither_sta_encode.restype = ctypes.c_int
         L.nc_dither_sta_decode.restype = ctypes.c_int
         L.nc_aggregate_sum.argtypes = [ctypes.POINTER(AggDesc), _vp, _vp]
@@ -231,8 +234,9 @@ def dither_encode(x, p, s, seed, worker=0, index_offset=0, seg_offsets=None, buc
 
 
 def dither_decode(norms, code, sign, d, s, seg_offsets=None, bucket=0, out=None, standard=False):
-    """nc_dither_decode (standard=True: nc_dither_sta_decode)."""
-    norms = _dev(norms, torch.float32, "norms")
+    """nc_dither_decode (standard=True: nc_dither_sta_decode; uint8 norms: nc_dither_decode_norm8)."""
+    norm8 = norms.dtype == torch.uint8
+    norms = _dev(norms, torch.uint8 if norm8 else torch.float32, "norms")
     code = _dev(code, torch.uint8, "code")
     sign = _dev(sign, torch.uint8, "sign")
     off, nseg, bucket, count = _segments(d, seg_offsets, bucket)
@@ -240,7 +244,8 @@ def dither_decode(norms, code, sign, d, s, seg_offsets=None, bucket=0, out=None,
     if out is None:
         out = torch.empty(d, dtype=torch.float32, device=code.device)
     _dev(out, torch.float32, "out")
-    fn = lib().nc_dither_sta_decode if standard else lib().nc_dither_decode
+    assert not (norm8 and standard)
+    fn = lib().nc_dither_decode_norm8 if norm8 else lib().nc_dither_sta_decode if standard else lib().nc_dither_decode
     _check(fn(_ptr(norms), _ptr(code), _ptr(sign), d, _ptr(off), nseg, bucket, s, _ptr(out), _stream()))
     return out
 
@@ -250,7 +255,7 @@ def aggregate_sum(kind, d, code, sign=None, norms=None, s=0, seg_offsets=None, b
     """nc_aggregate_sum over the rows of 2-D plane tensors (row w = worker w)."""
     code = _dev(code, torch.uint8, "code")
     sign = _dev(sign, torch.uint8, "sign")
-    norms = _dev(norms, torch.float32, "norms")
+    norms = _dev(norms, torch.uint8 if kind == NC_KIND_DITHER_NORM8 else torch.float32, "norms")
     assert code.dim() == 2
     n = code.shape[0]
     desc = AggDesc()
@@ -259,7 +264,7 @@ def aggregate_sum(kind, d, code, sign=None, norms=None, s=0, seg_offsets=None, b
     if sign is not None:
         assert sign.dim() == 2 and sign.shape[0] == n
         desc.sign, desc.sign_stride = sign.data_ptr(), sign.shape[1]
-    if kind in (NC_KIND_DITHER, NC_KIND_DITHER_STA):
+    if kind in (NC_KIND_DITHER, NC_KIND_DITHER_STA, NC_KIND_DITHER_NORM8):
         off, nseg, bucket, count = _segments(d, seg_offsets, bucket)
         assert norms is not None and norms.dim() == 2 and norms.shape[0] == n and norms.shape[1] >= count
         desc.norms, desc.norm_stride = norms.data_ptr(), norms.shape[1]

@@ -360,6 +360,46 @@ def test_compressed_norm(nc, oracle, wl):
     assert np.array_equal(host(e2), eo2) and np.array_equal(host(q2).view(np.uint32), qo2.view(np.uint32))
 
 
+@pytest.mark.parametrize("s,bucket,n", [(4, 8192, 8), (8, 512, 3), (8, 96, 2), (20, 0, 2), (100, 64, 5), (127, 4096, 1)])
+def test_decoding_from_8_bit_norms(nc, oracle, wl, s, bucket, n):
+    """The exponent bytes of the compressed norms go straight into the decoder and the fused sum
+    (kind NC_KIND_DITHER_NORM8): same bits as decoding with the power-of-two floats, which is the
+    oracle's decode.  Scales down to 1e-38 make products fall below the normal range (where an
+    exponent sum alone would be wrong), zero buckets have exponent byte 0."""
+    d = 5 * 8192 + 1234
+    layers = np.array([0, 1000, 1000, 30_000, d], np.uint64) if bucket == 0 else None
+    seg = {"bucket": bucket} if bucket else {"seg_offsets": dev(layers)}
+    oseg = {"bucket": bucket} if bucket else {"offsets": layers}
+    nseg = nc.segment_count(d, 0 if layers is None else layers.size - 1, bucket, layers is not None)
+    nsign = nc.dither_sign_bytes(d, s)
+    e_all = torch.zeros((n, nseg + 3), dtype=torch.uint8, device="cuda")
+    code = torch.zeros((n, nc.plane_stride(nc.dither_code_bytes(d, s))), dtype=torch.uint8, device="cuda")
+    sign = torch.zeros((n, nc.plane_stride(max(nsign, 1))), dtype=torch.uint8, device="cuda")
+    rng = np.random.default_rng(s)
+    dec = []
+    for w in range(n):
+        block_scale = np.exp2(rng.choice([-124.0, -60.0, 0.0], size=d // 64 + 1))     # whole buckets of tiny values
+        x = (rng.standard_normal(d) * np.repeat(block_scale, 64)[:d]).astype(np.float32)
+        x[2048:4096] = 0.0
+        norms, _, _ = nc.dither_encode(dev(x), INF, s, 7, worker=w, norms_out=None, code_out=code[w, :nc.dither_code_bytes(d, s)],
+                                       sign_out=sign[w, :nsign] if nsign else None, **seg)
+        e, q = nc.norm_compress(norms, seed=7, worker=w)
+        e_all[w, :nseg] = e
+        eo, qo = oracle.norm_compress(host(norms), 7, w)
+        assert np.array_equal(host(e), eo)
+        yo = oracle.dither_decode(qo, host(code[w]), host(sign[w]) if nsign else None, d, s, **oseg)
+        y8 = nc.dither_decode(e, code[w], sign[w] if nsign else None, d, s, **seg)
+        assert np.array_equal(host(y8).view(np.uint32), yo.view(np.uint32)), w
+        dec.append(yo)
+    got = host(nc.aggregate_sum(nc.NC_KIND_DITHER_NORM8, d, code, sign if nsign else None, e_all, s=s, **seg))
+    seq = dec[0].copy()
+    for w in range(1, n):
+        seq = (seq + dec[w]).astype(np.float32)
+    assert np.array_equal(got.view(np.uint32), seq.view(np.uint32))
+    if bucket == 64:          # whole buckets of tiny values: results below the normal range do occur
+        assert any((np.abs(y[y != 0]) < 1.2e-38).any() for y in dec)
+
+
 @pytest.mark.parametrize("s", [4, 8, 100])
 def test_words_at_the_threshold(nc, oracle, s):
     """Inputs built from the random words (max-norm 1, so y = |x|): in the geometric region a
