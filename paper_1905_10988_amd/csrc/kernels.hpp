@@ -118,6 +118,7 @@ hipError_t launch_clip_aggregate(const ClipAggregateArgs& a, bool fast, hipStrea
 // `fast` promises the alignment the vector path needs (checked by the caller).
 hipError_t launch_nat_encode(const NatEncodeArgs& a, uint32_t n, bool fast, hipStream_t stream);
 hipError_t launch_nat_decode(const NatDecodeArgs& a, bool fast, hipStream_t stream);
-hipError_t launch_nat_aggregate(const NatAggregateArgs& a, bool fast, hipStream_t stream);
+// width: elements per lane the planes' alignment allows (16, 8) or 0 for any alignment.
+hipError_t launch_nat_aggregate(const NatAggregateArgs& a, int width, hipStream_t stream);
 
 }  // namespace natcomp

@@ -8,9 +8,13 @@
 //            t and t+128 of the tile, draws one Philox call per quad, stores its four
 //            exponent bytes as one word per quad; the four sign bits of 8 neighbouring
 //            lanes are gathered with DPP row shifts into one word stored by every 8th lane;
-//   decoder / aggregate  lane t reads 8 exponent bytes and one sign byte per worker, builds
-//            8 floats, and the workgroup transposes them through LDS so that each store
-//            instruction writes 16 contiguous bytes per lane.
+//   decoder  lane t reads 8 exponent bytes and one sign byte, builds 8 floats, and the
+//            workgroup transposes them through LDS so that each store instruction writes 16
+//            contiguous bytes per lane;
+//   aggregate  lane t owns 16 output elements: per worker one 16-byte exponent load and one
+//            2-byte sign load, all workers of a chunk of 8 in flight before the first add;
+//            the sums leave through the same kind of LDS transpose (planes that are only
+//            8-byte aligned take an 8-elements-per-lane kernel of the same shape).
 #include "device_common.hpp"
 #include "kernels.hpp"
 
@@ -204,11 +208,28 @@ __device__ __forceinline__ void nat_sum_chunk(const NatAggregateArgs& a, uint64_
     }
 }
 
+// Runs BODY<NW>(w0) over the workers in chunks of up to 8, in the order w = 0, 1, ..., n-1.
+#define NATCOMP_FOR_WORKER_CHUNKS(n, CALL)                        \
+    do {                                                          \
+        uint32_t w0 = 0;                                          \
+        for (; w0 + 8 <= (n); w0 += 8) { CALL(8); }               \
+        switch ((n) - w0) {                                       \
+            case 1: CALL(1); break;                               \
+            case 2: CALL(2); break;                               \
+            case 3: CALL(3); break;                               \
+            case 4: CALL(4); break;                               \
+            case 5: CALL(5); break;                               \
+            case 6: CALL(6); break;                               \
+            case 7: CALL(7); break;                               \
+            default: break;                                       \
+        }                                                         \
+    } while (0)
+
 // Fused decode-and-sum over n workers, 8 output elements per lane.  Workers are taken in
 // chunks of up to 8 whose loads are all issued before the first add, and added in the
 // fixed order w = 0, 1, ..., n-1 starting from worker 0's value.
 // Requires every worker's exponent plane 8-byte aligned and out 16-byte aligned.
-__global__ __launch_bounds__(kBlock) void nat_aggregate_kernel(NatAggregateArgs a) {
+__global__ __launch_bounds__(kBlock) void nat_aggregate8_kernel(NatAggregateArgs a) {
     __shared__ u32x4 lds[2 * kBlock];
     const uint64_t g0 = (uint64_t)blockIdx.x * kBlock;
     const uint64_t grp = g0 + threadIdx.x;
@@ -219,18 +240,9 @@ __global__ __launch_bounds__(kBlock) void nat_aggregate_kernel(NatAggregateArgs 
         // -0.0 is the identity of binary32 addition (x + -0.0 == x bit for bit, signed zeros
         // included), so starting there equals starting from worker 0's value.
         float acc[8] = {-0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f, -0.0f};
-        uint32_t w0 = 0;
-        for (; w0 + 8 <= a.n; w0 += 8) nat_sum_chunk<8>(a, grp, w0, acc);
-        switch (a.n - w0) {
-            case 1: nat_sum_chunk<1>(a, grp, w0, acc); break;
-            case 2: nat_sum_chunk<2>(a, grp, w0, acc); break;
-            case 3: nat_sum_chunk<3>(a, grp, w0, acc); break;
-            case 4: nat_sum_chunk<4>(a, grp, w0, acc); break;
-            case 5: nat_sum_chunk<5>(a, grp, w0, acc); break;
-            case 6: nat_sum_chunk<6>(a, grp, w0, acc); break;
-            case 7: nat_sum_chunk<7>(a, grp, w0, acc); break;
-            default: break;
-        }
+#define NATCOMP_CALL(NW) nat_sum_chunk<NW>(a, grp, w0, acc)
+        NATCOMP_FOR_WORKER_CHUNKS(a.n, NATCOMP_CALL);
+#undef NATCOMP_CALL
 #pragma unroll
         for (int j = 0; j < 8; ++j) bits[j] = f32_bits(acc[j]);
     }
@@ -238,6 +250,65 @@ __global__ __launch_bounds__(kBlock) void nat_aggregate_kernel(NatAggregateArgs 
     store_tile_transposed(lds, bits, have, full > g0 ? groups : 0u, a.out + g0 * 8);
     if (grp == full && (a.d & 7)) {
         for (uint64_t i = grp * 8; i < a.d; ++i) a.out[i] = nat_sum_one(a, i);
+    }
+}
+
+// NW workers starting at w0 for the lane's group of 16 elements: per worker one 16-byte
+// exponent load and one 2-byte sign load, all issued before the first add.
+template <int NW>
+__device__ __forceinline__ void nat_sum_chunk16(const NatAggregateArgs& a, uint64_t grp, uint32_t w0, float acc[16]) {
+    u32x4 e[NW];
+    uint32_t sb[NW];
+#pragma unroll
+    for (int k = 0; k < NW; ++k) {
+        const size_t w = w0 + k;
+        e[k] = load_stream(reinterpret_cast<const u32x4*>(a.exp + w * a.exp_stride) + grp);
+        sb[k] = load_stream(reinterpret_cast<const uint16_t*>(a.sign + w * a.sign_stride) + grp);
+    }
+#pragma unroll
+    for (int k = 0; k < NW; ++k) {
+        uint32_t v[8];
+        nat_decode8(u32x2{e[k].x, e[k].y}, sb[k], v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += bits_f32(v[j]);
+        nat_decode8(u32x2{e[k].z, e[k].w}, sb[k] >> 8, v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[8 + j] += bits_f32(v[j]);
+    }
+}
+
+// The same sum with 16 output elements per lane (a tile of 4096 per workgroup): wider loads,
+// half as many of them.  Requires every worker's exponent plane 16-byte aligned, every sign
+// plane 2-byte aligned and out 16-byte aligned.  Lane t puts its four result quads into LDS
+// slots 4t .. 4t+3; every store instruction then writes slots t + 256 m, 16 contiguous bytes
+// per lane.
+__global__ __launch_bounds__(kBlock) void nat_aggregate_kernel(NatAggregateArgs a) {
+    __shared__ u32x4 lds[4 * kBlock];
+    const uint64_t g0 = (uint64_t)blockIdx.x * kBlock;
+    const uint64_t grp = g0 + threadIdx.x;
+    const uint64_t full = a.d >> 4;  // whole groups of 16
+    if (grp < full) {
+        float acc[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[j] = -0.0f;  // the identity of binary32 addition
+#define NATCOMP_CALL(NW) nat_sum_chunk16<NW>(a, grp, w0, acc)
+        NATCOMP_FOR_WORKER_CHUNKS(a.n, NATCOMP_CALL);
+#undef NATCOMP_CALL
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            lds[4 * threadIdx.x + q] = u32x4{f32_bits(acc[4 * q]), f32_bits(acc[4 * q + 1]), f32_bits(acc[4 * q + 2]),
+                                             f32_bits(acc[4 * q + 3])};
+    }
+    __syncthreads();
+    const uint32_t groups = full > g0 ? (full - g0 < kBlock ? (uint32_t)(full - g0) : (uint32_t)kBlock) : 0u;
+    u32x4* __restrict__ o = reinterpret_cast<u32x4*>(a.out + g0 * 16);
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const uint32_t slot = threadIdx.x + m * kBlock;
+        if (slot < 4 * groups) store_stream(o + slot, lds[slot]);
+    }
+    if (grp == full && (a.d & 15)) {  // the ragged last group
+        for (uint64_t i = grp * 16; i < a.d; ++i) a.out[i] = nat_sum_one(a, i);
     }
 }
 
@@ -330,10 +401,16 @@ hipError_t launch_nat_decode(const NatDecodeArgs& a, bool fast, hipStream_t stre
     return hipGetLastError();
 }
 
-hipError_t launch_nat_aggregate(const NatAggregateArgs& a, bool fast, hipStream_t stream) {
+hipError_t launch_nat_aggregate(const NatAggregateArgs& a, int width, hipStream_t stream) {
     const dim3 grid = grid_for_groups(a.d, 1);
-    if (fast) nat_aggregate_kernel<<<grid, kBlock, 0, stream>>>(a);
-    else nat_aggregate_generic_kernel<<<grid, kBlock, 0, stream>>>(a);
+    if (width == 16) {  // one lane per group of 16 elements, the ragged last group included
+        const uint64_t groups = a.d / 16 + 1;
+        nat_aggregate_kernel<<<(unsigned)((groups + kBlock - 1) / kBlock), kBlock, 0, stream>>>(a);
+    } else if (width == 8) {
+        nat_aggregate8_kernel<<<grid, kBlock, 0, stream>>>(a);
+    } else {
+        nat_aggregate_generic_kernel<<<grid, kBlock, 0, stream>>>(a);
+    }
     return hipGetLastError();
 }
 

@@ -321,8 +321,11 @@ nc_status nc_aggregate_sum(const nc_agg_desc* desc, float* out, void* stream) {
         if (desc->n > 1 && (desc->code_stride < nc_nat_exp_bytes(desc->d) || desc->sign_stride < nc_sign_bytes(desc->d)))
             return NC_ERR_INVALID;
         NatAggregateArgs a{desc->code, desc->code_stride, desc->sign, desc->sign_stride, desc->n, desc->d, out};
-        const bool fast = aligned(desc->code, 8) && aligned(out, 16) && (desc->n == 1 || (desc->code_stride & 7) == 0);
-        return from_hip(launch_nat_aggregate(a, fast, (hipStream_t)stream));
+        const bool one = desc->n == 1;
+        const bool w8 = aligned(desc->code, 8) && aligned(out, 16) && (one || (desc->code_stride & 7) == 0);
+        const bool w16 = w8 && aligned(desc->code, 16) && aligned(desc->sign, 2) &&
+                         (one || ((desc->code_stride & 15) == 0 && (desc->sign_stride & 1) == 0));
+        return from_hip(launch_nat_aggregate(a, w16 ? 16 : w8 ? 8 : 0, (hipStream_t)stream));
     }
     return dither_aggregate(desc->kind == NC_KIND_DITHER_STA ? 1u : 0u, desc->kind == NC_KIND_DITHER_NORM8 ? 1u : 0u, desc->norms, desc->norm_stride, desc->code, desc->code_stride, desc->sign,
                             desc->sign_stride, desc->n, desc->d, desc->seg_offsets, desc->num_segments, desc->bucket,

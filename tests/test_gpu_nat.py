@@ -158,6 +158,33 @@ def test_aggregate_odd_strides_and_cancellation(nc, oracle):
     assert np.all(first_two == 0)
 
 
+@pytest.mark.parametrize("exp_shift,exp_pad,sign_shift,sign_pad", [(0, 0, 0, 0), (8, 8, 0, 1), (16, 16, 1, 0), (8, 24, 2, 2),
+                                                                    (4, 4, 0, 0), (0, 8, 3, 3)])
+@pytest.mark.parametrize("d,n", [(20011, 8), (4096, 3), (70000, 11)])
+def test_aggregate_plane_alignments(nc, oracle, d, n, exp_shift, exp_pad, sign_shift, sign_pad):
+    """The fused sum picks a kernel by the planes' alignment (16 elements per lane for 16-byte
+    aligned exponent planes and even sign strides, 8 per lane for 8-byte alignment, one lane per
+    group otherwise): every choice gives the oracle's sum, ragged tail included."""
+    rng = np.random.default_rng(d + n)
+    es = (d + 15) // 16 * 16 + exp_pad
+    ss = ((d + 7) // 8 + 1) // 2 * 2 + sign_pad
+    exp_h = rng.integers(90, 140, (n, es)).astype(np.uint8)
+    sign_h = rng.integers(0, 256, (n, ss)).astype(np.uint8)
+    exp_raw = torch.zeros(n * es + 64, dtype=torch.uint8, device="cuda")
+    sign_raw = torch.zeros(n * ss + 64, dtype=torch.uint8, device="cuda")
+    exp = exp_raw[exp_shift: exp_shift + n * es].view(n, es)
+    sign = sign_raw[sign_shift: sign_shift + n * ss].view(n, ss)
+    exp.copy_(dev(exp_h))
+    sign.copy_(dev(sign_h))
+    out = Guarded(d, torch.float32)
+    nc.aggregate_sum(nc.NC_KIND_NAT, d, exp, sign, out=out.t)
+    torch.cuda.synchronize()
+    got = out.check()
+    o64, o32, oa = oracle.aggregate_nat(exp_h, sign_h, d)
+    assert np.array_equal(got.view(np.uint32), o32.view(np.uint32))
+    assert np.all(np.abs(got.astype(np.float64) - o64) <= 1e-5 * oa)
+
+
 def test_config2_full_size(nc, oracle, wl):
     """Config 2 at its full size and in the launch shape the benchmark times: d = 25,557,032
     in 161 layers, 8 workers encoded by one batched call, then the fused decode+sum.  Two
