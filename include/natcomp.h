@@ -129,6 +129,32 @@ nc_status nc_dither_encode(const float *x, uint64_t d, const uint64_t *seg_offse
                            uint64_t index_offset, float *norms_out, uint8_t *code_out, uint8_t *sign_out,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* nc_dither_encode for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments (without the workspace), same kernels and bit-identical outputs; the scratch
+ * memory is a static device array of nc_static_scratch_bytes() = 4 MiB that every GPU the
+ * library runs on holds until the process ends.  The call allocates nothing and frees nothing.
+ *   - nc_static_scratch_init() looks up the array's address on the current device (the HIP
+ *     runtime places the array in device memory at that moment, once per device and process).
+ *     Call it at set-up, with the device current, before a region that must not touch the
+ *     allocator (a graph capture, say); otherwise the first nc_dither_encode_static call on a
+ *     device does the same.  NC_OK, or NC_ERR_LAUNCH if the runtime cannot resolve the address.
+ *   - A description whose nc_dither_workspace_bytes(...) exceeds nc_static_scratch_bytes()
+ *     is rejected with NC_ERR_WORKSPACE and nothing is enqueued (use nc_dither_encode then):
+ *     with segment offsets this allows about d <= 2.5e8 with up to 65,536 segments;
+ *     descriptions that need no workspace (fixed buckets of at most 8192 elements that are a
+ *     multiple of 8) are never rejected for size.
+ *   - All calls on one GPU share that GPU's array: calls that may run concurrently (different
+ *     streams, different host threads) race on it and must be serialised by the caller.  The
+ *     array keeps the previous call's contents; the kernels rewrite every slot they read.
+ *   - NC_ERR_LAUNCH if the runtime cannot resolve the array's address. */
+size_t nc_static_scratch_bytes(void);
+nc_status nc_static_scratch_init(void);
+nc_status nc_dither_encode_static(const float *x, uint64_t d, const uint64_t *seg_offsets, uint32_t num_segments,
+                                  uint32_t bucket, float p, uint32_t s, uint64_t seed, uint32_t worker,
+                                  uint64_t index_offset, float *norms_out, uint8_t *code_out, uint8_t *sign_out,
+                                  void *stream);
+
 /* Decoder: out_i = sign * fl(norm_segment * 2^(c-s)), a signed zero for c = 0 (multiplying by
  * the level is an exponent addition, Sec. 3 and the fast-aggregation remark). */
 nc_status nc_dither_decode(const float *norms, const uint8_t *code, const uint8_t *sign, uint64_t d,

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 
+#include <atomic>
+
 #include "kernels.hpp"
 
 using namespace natcomp;
@@ -13,6 +15,26 @@ namespace {
 
 // A launch may hold at most 2^32 - 1 lanes; the vector kernels give a lane 4 to 32 elements.
 constexpr uint64_t kMaxD = 1ull << 34;
+
+// Scratch memory of nc_dither_encode_static: one array per GPU, held until the process ends.
+// The name is a host-side stand-in; the device address comes from hipGetSymbolAddress, once
+// per device, and only that address is ever passed to a kernel.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_address[kMaxDevices];
+
+// Address of `scratch` on the current device (nullptr if the runtime cannot tell).
+void* static_scratch_address() {
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return nullptr;
+    void* p = g_scratch_address[device].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+        g_scratch_address[device].store(p, std::memory_order_release);  // every thread finds the same address
+    }
+    return p;
+}
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 inline nc_status from_hip(hipError_t e) { return e == hipSuccess ? NC_OK : NC_ERR_LAUNCH; }
@@ -122,7 +144,8 @@ size_t nc_dither_workspace_bytes(uint64_t d, uint32_t num_segments, uint32_t buc
 static nc_status dither_encode(uint32_t standard, const float* x, uint64_t d, const uint64_t* seg_offsets,
                                uint32_t num_segments, uint32_t bucket, float p, uint32_t s, uint64_t seed,
                                uint32_t worker, uint64_t index_offset, float* norms_out, uint8_t* code_out,
-                               uint8_t* sign_out, void* workspace, size_t workspace_bytes, void* stream) {
+                               uint8_t* sign_out, void* workspace, size_t workspace_bytes, void* stream,
+                               bool static_scratch = false) {
     if (!(standard ? valid_s_size(s) : valid_s(s)) || d > kMaxD) return NC_ERR_INVALID;
     int pnorm;
     if (p == 1.0f) pnorm = kNormL1;
@@ -144,6 +167,12 @@ static nc_status dither_encode(uint32_t standard, const float* x, uint64_t d, co
     if (one_pass_bucket(seg_offsets, bucket))
         return from_hip(launch_dither_bucket_encode(a, fast, (hipStream_t)stream));
     const size_t need = nc_dither_workspace_bytes(d, num_segments, bucket, seg_offsets != nullptr);
+    if (static_scratch) {  // the library's own array instead of a caller workspace
+        if (need > kStaticScratchBytes) return NC_ERR_WORKSPACE;
+        workspace = static_scratch_address();
+        if (!workspace) return NC_ERR_LAUNCH;
+        workspace_bytes = kStaticScratchBytes;
+    }
     if (!workspace || workspace_bytes < need || !aligned(workspace, 8)) return NC_ERR_WORKSPACE;
     const uint64_t nseg = nc_segment_count(d, num_segments, bucket, seg_offsets != nullptr);
     const uint64_t chunks = (d + kNormChunk - 1) / kNormChunk;
@@ -162,6 +191,18 @@ nc_status nc_dither_encode(const float* x, uint64_t d, const uint64_t* seg_offse
                            void* workspace, size_t workspace_bytes, void* stream) {
     return dither_encode(0, x, d, seg_offsets, num_segments, bucket, p, s, seed, worker, index_offset, norms_out,
                          code_out, sign_out, workspace, workspace_bytes, stream);
+}
+
+size_t nc_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+nc_status nc_static_scratch_init(void) { return static_scratch_address() ? NC_OK : NC_ERR_LAUNCH; }
+
+nc_status nc_dither_encode_static(const float* x, uint64_t d, const uint64_t* seg_offsets, uint32_t num_segments,
+                                  uint32_t bucket, float p, uint32_t s, uint64_t seed, uint32_t worker,
+                                  uint64_t index_offset, float* norms_out, uint8_t* code_out, uint8_t* sign_out,
+                                  void* stream) {
+    return dither_encode(0, x, d, seg_offsets, num_segments, bucket, p, s, seed, worker, index_offset, norms_out,
+                         code_out, sign_out, nullptr, 0, stream, /*static_scratch=*/true);
 }
 
 nc_status nc_dither_sta_encode(const float* x, uint64_t d, const uint64_t* seg_offsets, uint32_t num_segments,

@@ -65,6 +65,13 @@ def lib():
         L.nc_nat_decode.argtypes = [_vp, _vp, _u64, _vp, _vp]
         L.nc_dither_encode.argtypes = [_vp, _u64, _vp, _u32, _u32, ctypes.c_float, _u32, _u64, _u32, _u64,
                                        _vp, _vp, _vp, _vp, _sz, _vp]
+        L.nc_dither_encode_static.argtypes = [_vp, _u64, _vp, _u32, _u32, ctypes.c_float, _u32, _u64, _u32, _u64,
+                                              _vp, _vp, _vp, _vp]
+        L.nc_dither_encode_static.restype = ctypes.c_int
+        L.nc_static_scratch_init.argtypes = []
+        L.nc_static_scratch_init.restype = ctypes.c_int
+        L.nc_static_scratch_bytes.argtypes = []
+        L.nc_static_scratch_bytes.restype = _sz
         L.nc_dither_decode.argtypes = [_vp, _vp, _vp, _u64, _vp, _u32, _u32, _u32, _vp, _vp]
         L.nc_dither_sta_encode.argtypes = L.nc_dither_encode.argtypes
         L.nc_dither_sta_decode.argtypes = L.nc_dither_decode.argtypes
@@ -230,6 +237,31 @@ def dither_encode(x, p, s, seed, worker=0, index_offset=0, seg_offsets=None, buc
     _check(fn(_ptr(x), d, _ptr(off), nseg, bucket, float(p), s, seed, worker, index_offset,
               _ptr(norms_out), _ptr(code_out), _ptr(sign_out), _ptr(workspace),
               0 if workspace is None else workspace.numel(), _stream()))
+    return norms_out, code_out, sign_out
+
+
+def static_scratch_bytes():
+    return lib().nc_static_scratch_bytes()
+
+
+def static_scratch_init():
+    """nc_static_scratch_init on torch's current device."""
+    _check(lib().nc_static_scratch_init())
+
+
+def dither_encode_static(x, p, s, seed, norms_out, code_out, sign_out=None, worker=0, index_offset=0,
+                         seg_offsets=None, bucket=0):
+    """nc_dither_encode_static: every output is the caller's; nothing is allocated here or in the library."""
+    x = _dev(x, torch.float32, "x")
+    d = x.numel()
+    off, nseg, bucket, count = _segments(d, seg_offsets, bucket)
+    _dev(norms_out, torch.float32, "norms_out")
+    _dev(code_out, torch.uint8, "code_out")
+    _dev(sign_out, torch.uint8, "sign_out")
+    assert norms_out.numel() >= count and code_out.numel() >= dither_code_bytes(d, s)
+    assert dither_sign_bytes(d, s) == 0 or (sign_out is not None and sign_out.numel() >= dither_sign_bytes(d, s))
+    _check(lib().nc_dither_encode_static(_ptr(x), d, _ptr(off), nseg, bucket, float(p), s, seed, worker, index_offset,
+                                         _ptr(norms_out), _ptr(code_out), _ptr(sign_out), _stream()))
     return norms_out, code_out, sign_out
 
 

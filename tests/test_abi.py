@@ -90,6 +90,11 @@ def test_more_argument_errors_without_touching_the_gpu(nc):
     assert L.nc_dither_encode(one, 8, None, 0, 0, 2.0, 8, 0, 0, 0, one, one, one, None, 0, None) == 4    # whole-vector norm: workspace
     assert L.nc_dither_encode(one, 8, one, 0, 0, 2.0, 8, 0, 0, 0, one, one, one, one, 1 << 20, None) == 2  # offsets with 0 segments
     assert L.nc_dither_encode(None, 0, None, 0, 0, 2.0, 8, 0, 0, 0, None, None, None, None, 0, None) == 0
+    # the static-scratch variant refuses, before touching the GPU, what its 4 MiB array cannot hold
+    assert nc.static_scratch_bytes() == 4 << 20
+    assert nc.dither_workspace_bytes(64, 1 << 20, 0, True) > nc.static_scratch_bytes()
+    assert L.nc_dither_encode_static(one, 64, one, 1 << 20, 0, 2.0, 8, 0, 0, 0, one, one, one, None) == 4
+    assert L.nc_dither_encode_static(one, 8, None, 0, 0, 3.0, 8, 0, 0, 0, one, one, one, None) == 3
     # workspace: partial norms per 8192 elements, per-segment slots, and with offsets one record per 2048 elements
     assert nc.dither_workspace_bytes(10000, 0, 0, False) == 8 * 2 + 8 * 1 + 8
     assert nc.dither_workspace_bytes(10000, 3, 0, True) == 8 * 2 + 8 * 3 + 16 + 16 * 5
