@@ -1,0 +1,92 @@
+"""GPU parity at the shapes and launch configurations bench.py times for configurations 4 and 5:
+all 8 workers at full size, inputs drawn on the device by the same generators the benchmark uses.
+The oracle recomputes sampled windows (whole buckets / message ranges / output ranges) on their
+own, which it can because every random word depends on the element's global index only."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def nc():
+    from paper_1905_10988_amd import natcomp
+    natcomp.lib()
+    assert torch.cuda.is_available()
+    return natcomp
+
+
+@pytest.fixture(scope="module")
+def wl():
+    from paper_1905_10988_amd import workloads
+    return workloads
+
+
+def test_config4_eight_workers_full_size(nc, oracle, wl):
+    """Config 4: D_nat^{inf,4}, buckets of 8192, d = 138,357,544, 8 workers encoded one launch each,
+    then the fused decode+sum n = 8.  Norms, codes and the sum on sampled windows of whole buckets
+    (the first, the ragged last, and random ones) against the oracle."""
+    d, bucket, s, n = wl.D_VGG16, wl.BUCKET, 4, wl.NUM_WORKERS
+    nb = nc.segment_count(d, 0, bucket, False)
+    x = torch.empty((n, d), dtype=torch.float32, device="cuda")
+    for w in range(n):
+        wl.bucketed_gaussian_device(w, out=x[w])
+    norms = torch.empty((n, nb), dtype=torch.float32, device="cuda")
+    code = torch.empty((n, nc.plane_stride(nc.dither_code_bytes(d, s))), dtype=torch.uint8, device="cuda")
+    for w in range(n):
+        nc.dither_encode(x[w], math.inf, s, 0, worker=w, bucket=bucket, norms_out=norms[w], code_out=code[w])
+    out = torch.empty(d, dtype=torch.float32, device="cuda")
+    nc.aggregate_sum(nc.NC_KIND_DITHER, d, code, None, norms, s=s, bucket=bucket, out=out)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4)
+    first_buckets = [0, nb - 3] + rng.integers(1, nb - 4, 6).tolist()       # windows of 3 buckets; one holds the ragged end
+    for b0 in first_buckets:
+        a, e = b0 * bucket, min((b0 + 3) * bucket, d)
+        m = e - a
+        gn = host(norms[:, b0: b0 + 3])
+        codes_o = []
+        for w in range(n):
+            xw = host(x[w, a:e])
+            ref = oracle.pnorm_segments(xw, math.inf, bucket=bucket)
+            assert np.array_equal(gn[w, : ref.size].astype(np.float64), ref), (b0, w)
+            co, _ = oracle.dither_encode(xw, s, gn[w, : ref.size], 0, w, index_offset=a, bucket=bucket)
+            assert np.array_equal(host(code[w, a // 2: a // 2 + co.size]), co), (b0, w)
+            codes_o.append(co)
+        nseg_w = -(-m // bucket)
+        o64, o32, oa = oracle.aggregate_dither(gn[:, :nseg_w], np.stack(codes_o), None, m, s, bucket=bucket)
+        got = host(out[a:e])
+        assert np.array_equal(got.view(np.uint32), o32.view(np.uint32)), b0
+        assert np.all(np.abs(got.astype(np.float64) - o64) <= 1e-5 * oa)
+
+
+def test_config5_eight_workers_full_size(nc, oracle, wl):
+    """Config 5: C_nat o S^k with d = 335,000,000, k = d/100, 8 workers encoded in one launch, then the
+    dense scatter-sum.  Every worker's whole message (indices, exponent bytes, sign bits) against the
+    oracle's, and the whole dense sum against the oracle's worker-ordered binary32 sum."""
+    d, n = wl.D_BERT_LARGE, wl.NUM_WORKERS
+    k = d // 100
+    scale = np.float32(d / k)
+    x = torch.empty((n, d), dtype=torch.float32, device="cuda")
+    for w in range(n):
+        wl.dense_gaussian_device(w, out=x[w])
+    idx, exp, sign = nc.sparse_nat_encode_batch(x, k, float(scale), 0)
+    out = nc.sparse_nat_aggregate(idx, exp, sign, k, d)
+    torch.cuda.synchronize()
+    ih, eh, sh = host(idx).view(np.uint32), host(exp), host(sign)
+    for w in range(n):
+        xw = host(x[w])
+        io, eo, so = oracle.sparse_nat_encode(xw, k, scale, 0, w)
+        del xw
+        assert np.array_equal(ih[w, :k], io), w
+        assert np.array_equal(eh[w, :k], eo), w
+        assert np.array_equal(sh[w, : so.size], so), w
+    del x
+    o32, _, _ = oracle.sparse_nat_aggregate(ih, eh, sh, k, d, only32=True)
+    got = host(out)
+    assert np.array_equal(got.view(np.uint32), o32.view(np.uint32))
+    assert 0.95 * n * k < np.count_nonzero(got) <= n * k

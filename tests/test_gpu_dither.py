@@ -103,6 +103,26 @@ def test_layer_segments(nc, oracle, wl):
     roundtrip(nc, oracle, x, 2, 8, offsets=np.array([0, d], np.uint64))
 
 
+def test_empty_segments_on_chunk_boundaries(nc, oracle, wl):
+    """Empty segments whose offset is the first element of the vector, of a 2048-element encode
+    chunk, of a 4096-element norm chunk, or the end of the vector, and segments that begin
+    exactly on those boundaries: every norm is written (0 for the empty ones; the guarded
+    buffer would show a skipped slot) and every code matches."""
+    d = 20_480 + 77
+    x = wl.bucketed_gaussian(1, d=d, bucket=500, seed=33)
+    off = np.array([0, 0, 0, 5, 2048, 2048, 2048, 3000, 4096, 4096, 6144, 8192, 8192, 8192, 12288, 12290, 12290,
+                    16384, d, d, d], np.uint64)
+    for p, s in [(2, 8), (INF, 4), (1, 20)]:
+        norms, _, _ = roundtrip(nc, oracle, x, p, s, offsets=off)
+        assert np.all(norms[np.diff(off.astype(np.int64)) == 0] == 0.0)
+    # a single long segment that starts on a chunk boundary after empties, and one that ends on one
+    off = np.array([0, 2048, 2048, 2048 + 8192, d], np.uint64)
+    roundtrip(nc, oracle, x, 2, 8, offsets=off)
+    # unaligned input pointer: the lane-by-lane path everywhere
+    base = np.concatenate([np.zeros(1, np.float32), x])
+    roundtrip(nc, oracle, x, 2, 8, offsets=off, xdev=dev(base)[1:])
+
+
 @pytest.mark.parametrize("bucket", [32, 64, 96, 128, 160, 256, 480, 512, 992, 1024, 1536, 2016, 2048, 4096, 8192])
 def test_buckets_sharing_a_workgroup(nc, oracle, wl, bucket):
     """The kernel that gives a bucket (a multiple of 32) to 8..64 lanes of a workgroup: whole tiles, a partial
