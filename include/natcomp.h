@@ -49,7 +49,8 @@ extern "C" {
 typedef enum {
     NC_OK = 0,
     NC_ERR_NULL = 1,        /* a required pointer is NULL */
-    NC_ERR_INVALID = 2,     /* n = 0, s outside 1..127, bad strides or segment description */
+    NC_ERR_INVALID = 2,     /* n = 0, s outside its range, bad strides or segment description, d beyond the
+                               maximum (d = 0 is not an error: the call returns NC_OK and does nothing) */
     NC_ERR_UNSUPPORTED = 3, /* p is not 1, 2 or INFINITY */
     NC_ERR_WORKSPACE = 4,   /* workspace missing or too small */
     NC_ERR_LAUNCH = 5       /* the HIP runtime refused a launch */

@@ -316,8 +316,8 @@ nc_status nc_master_nat(const nc_agg_desc* desc, uint64_t seed, uint32_t master,
 nc_status nc_nat_clip_encode(const float* x, size_t x_stride, uint32_t n, uint64_t d, uint64_t seed,
                              uint32_t first_worker, uint64_t index_offset, uint8_t* code_out, size_t code_stride,
                              void* stream) {
-    if (d > kMaxD || n > 65535) return NC_ERR_INVALID;
-    if (n == 0 || d == 0) return NC_OK;
+    if (n == 0 || d > kMaxD || n > 65535) return NC_ERR_INVALID;
+    if (d == 0) return NC_OK;
     if (!x || !code_out) return NC_ERR_NULL;
     if (n > 1 && (x_stride < d || code_stride < d)) return NC_ERR_INVALID;
     ClipEncodeArgs a{x, x_stride, d, (uint32_t)seed, (uint32_t)(seed >> 32), first_worker, index_offset, code_out,

@@ -232,7 +232,8 @@ def dither_encode(x, p, s, seed, worker=0, index_offset=0, seg_offsets=None, buc
     _dev(code_out, torch.uint8, "code_out")
     _dev(sign_out, torch.uint8, "sign_out")
     _dev(workspace, torch.uint8, "workspace")
-    assert norms_out.numel() >= count
+    assert norms_out.numel() >= count and code_out.numel() >= dither_code_bytes(d, s)
+    assert nsign == 0 or sign_out.numel() >= nsign
     fn = lib().nc_dither_sta_encode if standard else lib().nc_dither_encode
     _check(fn(_ptr(x), d, _ptr(off), nseg, bucket, float(p), s, seed, worker, index_offset,
               _ptr(norms_out), _ptr(code_out), _ptr(sign_out), _ptr(workspace),
@@ -272,10 +273,12 @@ def dither_decode(norms, code, sign, d, s, seg_offsets=None, bucket=0, out=None,
     code = _dev(code, torch.uint8, "code")
     sign = _dev(sign, torch.uint8, "sign")
     off, nseg, bucket, count = _segments(d, seg_offsets, bucket)
-    assert norms.numel() >= count
+    assert norms.numel() >= count and code.numel() >= dither_code_bytes(d, s)
+    assert dither_sign_bytes(d, s) == 0 or (sign is not None and sign.numel() >= dither_sign_bytes(d, s))
     if out is None:
         out = torch.empty(d, dtype=torch.float32, device=code.device)
     _dev(out, torch.float32, "out")
+    assert out.numel() >= d
     assert not (norm8 and standard)
     fn = lib().nc_dither_decode_norm8 if norm8 else lib().nc_dither_sta_decode if standard else lib().nc_dither_decode
     _check(fn(_ptr(norms), _ptr(code), _ptr(sign), d, _ptr(off), nseg, bucket, s, _ptr(out), _stream()))
@@ -296,7 +299,11 @@ def aggregate_sum(kind, d, code, sign=None, norms=None, s=0, seg_offsets=None, b
     if sign is not None:
         assert sign.dim() == 2 and sign.shape[0] == n
         desc.sign, desc.sign_stride = sign.data_ptr(), sign.shape[1]
+    if kind == NC_KIND_NAT:
+        assert code.shape[1] >= nat_exp_bytes(d) and sign is not None and sign.shape[1] >= sign_bytes(d)
     if kind in (NC_KIND_DITHER, NC_KIND_DITHER_STA, NC_KIND_DITHER_NORM8):
+        assert code.shape[1] >= dither_code_bytes(d, s)
+        assert dither_sign_bytes(d, s) == 0 or (sign is not None and sign.shape[1] >= dither_sign_bytes(d, s))
         off, nseg, bucket, count = _segments(d, seg_offsets, bucket)
         assert norms is not None and norms.dim() == 2 and norms.shape[0] == n and norms.shape[1] >= count
         desc.norms, desc.norm_stride = norms.data_ptr(), norms.shape[1]
@@ -318,6 +325,7 @@ def sparse_nat_encode_batch(x, k, scale, seed, first_worker=0, d=None, idx_out=N
     assert x.dim() == 2
     n, row = x.shape
     d = row if d is None else d
+    assert 0 < k <= d <= row
     if idx_out is None:
         idx_out = torch.empty((n, plane_stride(4 * k) // 4), dtype=torch.int32, device=x.device)
     if exp_out is None:
@@ -327,7 +335,8 @@ def sparse_nat_encode_batch(x, k, scale, seed, first_worker=0, d=None, idx_out=N
     _dev(idx_out, torch.int32, "idx_out")
     _dev(exp_out, torch.uint8, "exp_out")
     _dev(sign_out, torch.uint8, "sign_out")
-    assert idx_out.shape[0] == n and idx_out.shape[1] >= k and exp_out.shape[1] >= k
+    assert idx_out.shape[0] == n and exp_out.shape[0] == n and sign_out.shape[0] == n
+    assert idx_out.shape[1] >= k and exp_out.shape[1] >= k and sign_out.shape[1] >= sign_bytes(k)
     _check(lib().nc_sparse_nat_encode_batch(_ptr(x), row, n, d, k, float(scale), seed, first_worker, _ptr(idx_out),
                                             idx_out.shape[1], _ptr(exp_out), exp_out.shape[1], _ptr(sign_out),
                                             sign_out.shape[1], _stream()))
@@ -338,6 +347,8 @@ def sparse_nat_encode(x, k, scale, seed, worker=0):
     """nc_sparse_nat_encode on a 1-D tensor: (idx (k,), exp (k,), sign (ceil(k/8),))."""
     x = _dev(x, torch.float32, "x")
     d = x.numel()
+    if not 0 < k <= d:
+        raise NatcompError("NC_ERR_INVALID")
     idx = torch.empty(k, dtype=torch.int32, device=x.device)
     exp = torch.empty(k, dtype=torch.uint8, device=x.device)
     sign = torch.empty(sign_bytes(k), dtype=torch.uint8, device=x.device)
@@ -353,6 +364,8 @@ def sparse_nat_aggregate(idx, exp, sign, k, d, out=None):
     sign = _dev(sign, torch.uint8, "sign")
     assert idx.dim() == 2 and exp.dim() == 2 and sign.dim() == 2
     n = idx.shape[0]
+    assert exp.shape[0] == n and sign.shape[0] == n
+    assert idx.shape[1] >= k and exp.shape[1] >= k and sign.shape[1] >= sign_bytes(k)
     if out is None:
         out = torch.empty(d, dtype=torch.float32, device=idx.device)
     _dev(out, torch.float32, "out")

@@ -102,7 +102,8 @@ def test_more_argument_errors_without_touching_the_gpu(nc):
     # clipped bytes and the integer sum
     assert L.nc_nat_clip_encode(None, 0, 1, 8, 0, 0, 0, one, 0, None) == 1
     assert L.nc_nat_clip_encode(one, 4, 2, 8, 0, 0, 0, one, 8, None) == 2          # x stride below d
-    assert L.nc_nat_clip_encode(None, 0, 0, 8, 0, 0, 0, None, 0, None) == 0        # no workers: nothing to do
+    assert L.nc_nat_clip_encode(one, 0, 0, 8, 0, 0, 0, one, 0, None) == 2          # no workers
+    assert L.nc_nat_clip_encode(None, 0, 1, 0, 0, 0, 0, None, 0, None) == 0        # d = 0: nothing to do
     assert L.nc_nat_clip_decode(None, 8, one, None) == 1
     assert L.nc_clip_aggregate_int(one, 8, 0, 8, 0, 0, 0, one, one, one, None) == 2
     assert L.nc_clip_aggregate_int(one, 8, 1, 8, 0, 0, 0, None, None, None, None) == 1   # no output at all

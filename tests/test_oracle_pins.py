@@ -418,7 +418,9 @@ def test_dithering_tends_to_natural_compression(oracle):
 
 def test_dither_normalisation(oracle):
     assert oracle.dither_inv_norm(0.0) == 0.0
-    assert oracle.dither_inv_norm(1e-39) == 0.0           # subnormal norm: segment treated as zero
+    # a reading of this build, not a statement of the paper (Def. 3 only says D(0) = 0): a norm below the
+    # smallest normal number has no binary32 reciprocal, so the segment is treated as the zero vector
+    assert oracle.dither_inv_norm(1e-39) == 0.0
     assert oracle.dither_inv_norm(4.0) == 0.25
     assert oracle.dither_inv_norm(3.0) == float(np.float32(1.0) / np.float32(3.0))
     inv = np.float32(oracle.dither_inv_norm(3.0))
@@ -431,6 +433,50 @@ def _dither_roundtrip(oracle, x, s, p, seed, offsets=None, bucket=0):
     norms = oracle.pnorm_segments(x, p, offsets=offsets, bucket=bucket).astype(np.float32)
     code, sign = oracle.dither_encode(x, s, norms, seed, offsets=offsets, bucket=bucket)
     return norms, code, sign, oracle.dither_decode(norms, code, sign, x.size, s, offsets=offsets, bucket=bucket)
+
+
+def test_packed_layouts_as_stated_in_the_header(oracle):
+    """The plane layouts are this build's choice (the paper fixes none); include/natcomp.h states
+    them, and this test builds the expected bytes from that statement alone: sign plane bit (i mod 8)
+    of byte i/8; exponent plane byte i; level codes as fused nibbles (sign << 3) | c for at most 3
+    bits per code, element i in byte i/2 with the low nibble for even i; a nibble plane plus sign
+    plane for 4 bits; a byte plane plus sign plane beyond.  The inputs sit exactly on levels
+    (x_i = +-2^(c_i - s) with max |x| = 1), so every code is certain whatever the random words."""
+    d = 13                                                   # odd: the last nibble and the last sign bits are padding
+    rng = np.random.default_rng(8)
+    sgn = rng.integers(0, 2, d).astype(np.uint32)
+    sign_plane = np.zeros((d + 7) // 8, np.uint8)
+    for i in range(d):
+        sign_plane[i // 8] |= np.uint8(int(sgn[i]) << (i % 8))
+    for s in (1, 3, 4, 7, 8, 15, 16, 40, 127):
+        c = rng.integers(1, s + 1, d).astype(np.uint32)
+        c[0] = s                                             # the maximum: the infinity-norm is 1
+        c[3] = 0                                             # and one exact zero
+        mag = np.where(c > 0, np.exp2(c.astype(np.float64) - s), 0.0)
+        x = (mag * np.where(sgn == 1, -1.0, 1.0)).astype(np.float32)
+        norms = oracle.pnorm_segments(x, math.inf).astype(np.float32)
+        assert norms[0] == 1.0
+        code, sign = oracle.dither_encode(x, s, norms, seed=int(s))
+        bits = int(np.ceil(np.log2(s + 1)))
+        if bits <= 3:
+            want = np.zeros((d + 1) // 2, np.uint8)
+            for i in range(d):
+                want[i // 2] |= np.uint8((((int(sgn[i]) << 3) | int(c[i])) << (4 * (i % 2))))
+            assert sign.size == 0
+        elif bits == 4:
+            want = np.zeros((d + 1) // 2, np.uint8)
+            for i in range(d):
+                want[i // 2] |= np.uint8(int(c[i]) << (4 * (i % 2)))
+            assert np.array_equal(sign, sign_plane)
+        else:
+            want = c.astype(np.uint8)
+            assert np.array_equal(sign, sign_plane)
+        assert np.array_equal(code, want), s
+    # C_nat planes: powers of two keep their exponent for every word
+    e = rng.integers(1, 255, d).astype(np.uint32)
+    x = ((sgn << 31) | (e << 23)).astype(np.uint32).view(np.float32)
+    exp, sign = oracle.nat_encode(x, seed=5)
+    assert np.array_equal(exp, e.astype(np.uint8)) and np.array_equal(sign, sign_plane)
 
 
 def test_dither_vector_brackets_and_layouts(oracle):
