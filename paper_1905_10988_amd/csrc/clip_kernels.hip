@@ -118,15 +118,16 @@ __device__ __forceinline__ uint64_t clip_units(uint32_t byte) {
     return (byte & 0x80u) ? 0ull - mag : mag;
 }
 
-// The same for byte j of a word, with fewer operations: +1, 0 or -1 (from the sign and zero
-// bits, sign-extended to 64 bits) shifted left by the field; a two's complement shift of -1
-// gives -2^field.
-__device__ __forceinline__ uint64_t clip_units_at(uint32_t word, int j) {
-    const uint32_t neg = (uint32_t)__builtin_amdgcn_sbfe((int32_t)word, 8 * j + 7, 1);  // 0 or all ones
-    const uint32_t zer = (uint32_t)__builtin_amdgcn_sbfe((int32_t)word, 8 * j + 6, 1);
-    const uint32_t lo = __builtin_amdgcn_bitop3_b32(neg, 1u, zer, 0x54);  // (neg | 1) & ~zer
-    const uint32_t hi = __builtin_amdgcn_bitop3_b32(neg, 0u, zer, 0x50);  // neg & ~zer: the sign extension
-    return (((uint64_t)hi << 32) | lo) << ((word >> (8 * j)) & 63u);
+// The same through a table in LDS: entry b is the 64-bit integer byte b stands for, so an
+// addend costs one byte-select-and-shift, one 8-byte LDS read and one 64-bit add.  (Built in
+// registers it is two sign-extracting field reads, two three-way logic operations and a 64-bit
+// shift before the add: this kernel is bound by VALU work, not by HBM.)
+__device__ __forceinline__ void clip_table_fill(uint64_t* table) {
+    table[threadIdx.x] = clip_units(threadIdx.x);  // kBlock = 256 lanes: one entry each
+    __syncthreads();
+}
+__device__ __forceinline__ uint64_t clip_units_at(const uint64_t* table, uint32_t word, int j) {
+    return table[(word >> (8 * j)) & 255u];
 }
 
 // C_nat of the integer sum: exponent field of the result (0 for a zero sum).  With
@@ -149,7 +150,8 @@ __device__ __forceinline__ uint64_t clip_sum_one(const ClipAggregateArgs& a, uin
 
 // NW workers starting at w0; all loads issued before the first add.
 template <int NW>
-__device__ __forceinline__ void clip_sum_chunk(const ClipAggregateArgs& a, uint64_t grp, uint32_t w0, uint64_t acc[8]) {
+__device__ __forceinline__ void clip_sum_chunk(const ClipAggregateArgs& a, const uint64_t* table, uint64_t grp,
+                                               uint32_t w0, uint64_t acc[8]) {
     u32x2 c[NW];
 #pragma unroll
     for (int k = 0; k < NW; ++k)
@@ -157,7 +159,7 @@ __device__ __forceinline__ void clip_sum_chunk(const ClipAggregateArgs& a, uint6
 #pragma unroll
     for (int k = 0; k < NW; ++k) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] += clip_units_at(j < 4 ? c[k].x : c[k].y, j & 3);
+        for (int j = 0; j < 8; ++j) acc[j] += clip_units_at(table, j < 4 ? c[k].x : c[k].y, j & 3);
     }
 }
 
@@ -165,14 +167,17 @@ __device__ __forceinline__ void clip_sum_chunk(const ClipAggregateArgs& a, uint6
 // aligned, sum_out (if given) 16-byte aligned, index_offset a multiple of 4.  One lane owns
 // 8 consecutive elements; the ragged last group goes element by element.
 __global__ __launch_bounds__(kBlock) void clip_aggregate_kernel(ClipAggregateArgs a) {
+    __shared__ uint64_t table[kBlock];
+    static_assert(kBlock == 256, "one table entry per lane");
+    clip_table_fill(table);
     const uint64_t grp = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
     const uint64_t full = a.d >> 3;
     if (grp < full) {
         uint64_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         uint32_t w0 = 0;
-        for (; w0 + 8 <= a.n; w0 += 8) clip_sum_chunk<8>(a, grp, w0, acc);
-        for (; w0 + 2 <= a.n; w0 += 2) clip_sum_chunk<2>(a, grp, w0, acc);
-        if (w0 < a.n) clip_sum_chunk<1>(a, grp, w0, acc);
+        for (; w0 + 8 <= a.n; w0 += 8) clip_sum_chunk<8>(a, table, grp, w0, acc);
+        for (; w0 + 2 <= a.n; w0 += 2) clip_sum_chunk<2>(a, table, grp, w0, acc);
+        if (w0 < a.n) clip_sum_chunk<1>(a, table, grp, w0, acc);
         if (a.sum_out) {
             typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
             u64x2* __restrict__ so = reinterpret_cast<u64x2*>(a.sum_out + grp * 8);
