@@ -48,6 +48,10 @@ def lib():
         L.orc_philox4x32_10.restype = None
         L.orc_random_word.argtypes = [_u64, _u32, _u32, _u64]
         L.orc_random_word.restype = _u32
+        L.orc_dither_word.argtypes = [_u64, _u32, _u64]
+        L.orc_dither_word.restype = _u32
+        L.orc_dither_word_of_call.argtypes = [_u32p, _u32]
+        L.orc_dither_word_of_call.restype = _u32
         L.orc_nat_round.argtypes = [_u32, _u32]
         L.orc_nat_round.restype = _u32
         L.orc_nat_count_up.argtypes = [_u32]
@@ -152,6 +156,17 @@ def random_word(seed, worker, domain, g):
 
 
 # ------------------------------------------------------------ natural compression
+def dither_word(seed, worker, g):
+    """The 32-bit word the dithering operators draw for global element g (one call per 8 elements)."""
+    return int(lib().orc_dither_word(seed, worker, g))
+
+
+def dither_word_of_call(words, j):
+    """Word of element j (0..7) of a group, given the four output words of the group's call."""
+    w = np.asarray(words, np.uint32)
+    return int(lib().orc_dither_word_of_call(_ptr(w, _u32p), j))
+
+
 def nat_round(u_bits, r):
     """New exponent field of the binary32 value with bits u_bits, given the uniform word r."""
     return int(lib().orc_nat_round(u_bits, r))

@@ -30,7 +30,8 @@
  *   orc_philox4x32_10    Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
  *                        as 1, 2, 3" (SC'11), Philox-4x32 with 10 rounds.  The paper only
  *                        asks for a Bernoulli draw per element; the generator, its keying by
- *                        (seed, worker, index) and the 32-bit comparison are this build's choice.
+ *                        (seed, worker, index), how many elements share a call and the width
+ *                        of the comparison are this build's choice.
  *
  * Parity status: every arithmetic rule here is pinned by tests against the
  * paper's worked examples, exact probabilities by exhaustive enumeration of
@@ -76,7 +77,9 @@ enum { ORC_DOMAIN_NAT = 0, ORC_DOMAIN_DITHER = 1, ORC_DOMAIN_MASTER = 3, ORC_DOM
 
 /* The 32-bit uniform word of global element g: the counter is (g/4, worker,
  * domain), the key is the seed, and the element takes output word g mod 4.
- * It depends on nothing but (seed, worker, domain, g). */
+ * It depends on nothing but (seed, worker, domain, g).  (Natural compression, the
+ * master's compression and the compressed norms draw this way; the dithering
+ * operators use orc_dither_word below.) */
 uint32_t orc_random_word(uint64_t seed, uint32_t worker, uint32_t domain, uint64_t g)
 {
     uint64_t q = g >> 2;
@@ -85,6 +88,35 @@ uint32_t orc_random_word(uint64_t seed, uint32_t worker, uint32_t domain, uint64
     uint32_t out[4];
     orc_philox4x32_10(ctr, key, out);
     return out[g & 3];
+}
+
+/* The dithering operators (domain 1) draw from a denser layout: one Philox call per 8
+ * consecutive elements, counter (g/8, worker, 1).  Elements 0..3 of the group share the
+ * words (a, b) = (w0, w1), elements 4..7 the words (a, b) = (w2, w3), and within such a
+ * half the four elements take a, b, a<<16 | b>>16 and b<<16 | a>>16.  Each of the four is a
+ * rearrangement of 32 distinct bits of the call's output, hence uniform on [0, 2^32) by
+ * itself; only the per-coordinate marginals enter the definition of the class B(omega)
+ * (Def. 2: unbiasedness and the second-moment bound are sums over coordinates), so the
+ * dependence between neighbours costs nothing there, and it is weak anyway: the top 23
+ * bits that decide two different elements share at most 7 bits. */
+uint32_t orc_dither_word_of_call(const uint32_t w[4], uint32_t j)
+{
+    uint32_t a = (j & 4) ? w[2] : w[0], b = (j & 4) ? w[3] : w[1];
+    switch (j & 3) {
+        case 0: return a;
+        case 1: return b;
+        case 2: return (a << 16) | (b >> 16);
+        default: return (b << 16) | (a >> 16);
+    }
+}
+uint32_t orc_dither_word(uint64_t seed, uint32_t worker, uint64_t g)
+{
+    uint64_t q = g >> 3;
+    uint32_t ctr[4] = { (uint32_t)q, (uint32_t)(q >> 32), worker, ORC_DOMAIN_DITHER };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    orc_philox4x32_10(ctr, key, out);
+    return orc_dither_word_of_call(out, (uint32_t)(g & 7));
 }
 
 static uint32_t f32_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
@@ -231,28 +263,42 @@ void orc_pnorm_segments(const float *x, uint64_t d, const uint64_t *offsets, uin
 
 /* Levels l_s = 0 < l_{s-1} = 2^(1-s) < ... < l_1 = 1/2 < l_0 = 1.  Level code
  * c in {0..s}: c = 0 is the level 0 and c >= 1 is 2^(c-s).  y in [0,1] is
- * given by its binary32 bits yb (sign cleared); r is a uniform 32-bit word.
- * With l_low <= y <= l_high adjacent levels, the result is l_high with
- * probability (y - l_low) / (l_high - l_low):
- *   y = 2^-k (1 + m/2^23), k <= s-1: between 2^-k and 2^(1-k), P(high) = m/2^23;
- *   y below the lowest level 2^(1-s):  between 0 and 2^(1-s), P(high) = y 2^(s-1).
- * Both are compared as integers against r/2^32; the second threshold is
- * truncated to a multiple of 2^-32.  y >= 1 (possible by one rounding of the
- * normalisation) is level 1; a subnormal or zero y is level 0. */
+ * given by its binary32 bits yb (sign cleared); r is a uniform 32-bit word, of
+ * which the top 23 bits r23 decide.  With l_low <= y <= l_high adjacent levels,
+ * the result is l_high with probability (y - l_low) / (l_high - l_low):
+ *   y = 2^-k (1 + m/2^23), k <= s-1: between 2^-k and 2^(1-k), P(high) = m/2^23,
+ *     exactly: high iff r23 < m;
+ *   y below the lowest level 2^(1-s): between 0 and 2^(1-s), P(high) = y 2^(s-1),
+ *     taken to 23 bits: high iff r23 < T with T = y 2^(s+22) rounded to the nearest
+ *     integer, ties to even (|T/2^23 - y 2^(s-1)| <= 2^-24; T = 2^23 means always).
+ *     For s <= 126 this T is the mantissa field of fl(y/2 + 2^-s), one fused
+ *     multiply-add: the same draw as in the geometric region, applied to a value that
+ *     carries y's position between 0 and 2^(1-s) in its mantissa.  It is evaluated
+ *     here in integers so that subnormal y and s = 127 need no special case.
+ * y >= 1 (possible by one rounding of the normalisation) is level 1. */
 uint32_t orc_dither_level(uint32_t yb, uint32_t s, uint32_t r)
 {
     if (yb >= 0x3F800000u) return s;
+    uint32_t r23 = r >> 9;
     uint32_t e_y = yb >> 23;
-    uint64_t m_y = yb & 0x7FFFFFu;
-    if (e_y == 0) return 0;
-    uint32_t k = 127u - e_y;                 /* 2^-k <= y < 2^(1-k), k >= 1 */
-    if (k <= s - 1) {
-        uint32_t up = ((uint64_t)r < (m_y << 9)) ? 1u : 0u;
-        return s - k + up;
+    uint32_t m_y = yb & 0x7FFFFFu;
+    if (e_y + s >= 128u) {                   /* 2^-k <= y < 2^(1-k) with k = 127 - e_y <= s - 1 */
+        uint32_t k = 127u - e_y;
+        return s - k + (r23 < m_y ? 1u : 0u);
     }
-    uint32_t sh = k - (s - 1);               /* y 2^(s-1) = (1 + m/2^23) 2^-sh, sh >= 1 */
-    uint64_t threshold = (sh > 40) ? 0 : (((0x800000u | m_y) << 9) >> sh);
-    return ((uint64_t)r < threshold) ? 1u : 0u;
+    /* y = M 2^(E-150) with E = max(e_y, 1); y 2^(s+22) = M / 2^sh, sh = 128 - s - E >= 0 */
+    uint64_t M = e_y ? (0x800000u | (uint64_t)m_y) : (uint64_t)m_y;
+    uint32_t sh = 128u - s - (e_y ? e_y : 1u);
+    uint64_t T;
+    if (sh == 0) {
+        T = M;
+    } else if (sh > 25) {
+        T = 0;                               /* M < 2^24: less than a quarter */
+    } else {
+        uint64_t q = M >> sh, rem = M & (((uint64_t)1 << sh) - 1), half = (uint64_t)1 << (sh - 1);
+        T = q + ((rem > half || (rem == half && (q & 1))) ? 1u : 0u);
+    }
+    return ((uint64_t)r23 < T) ? 1u : 0u;
 }
 
 /* Exhaustive count, over all 2^32 words r, of outcomes equal to `code`. */
@@ -344,7 +390,7 @@ void orc_dither_encode(const float *x, uint64_t d, const uint64_t *offsets, uint
         float inv = orc_dither_inv_norm(norms[sgm]);
         for (uint64_t i = b; i < e; ++i) {
             uint32_t yb = orc_dither_y_bits(x[i], inv);
-            uint32_t r = orc_random_word(seed, worker, ORC_DOMAIN_DITHER, index_offset + i);
+            uint32_t r = orc_dither_word(seed, worker, index_offset + i);
             uint32_t c = orc_dither_level(yb, s, r);
             put_code(code_out, sign_out, i, s, c, f32_bits(x[i]) >> 31);
         }
@@ -632,7 +678,7 @@ void orc_sta_encode(const float *x, uint64_t d, const uint64_t *offsets, uint32_
         float inv = orc_dither_inv_norm(norms[sgm]);
         for (uint64_t i = b; i < e; ++i) {
             volatile float y = fabsf(x[i]) * inv;
-            uint32_t r = orc_random_word(seed, worker, ORC_DOMAIN_DITHER, index_offset + i);
+            uint32_t r = orc_dither_word(seed, worker, index_offset + i);
             put_code(code_out, sign_out, i, s, orc_sta_level(y, s, r), f32_bits(x[i]) >> 31);
         }
     }

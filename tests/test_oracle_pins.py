@@ -374,12 +374,24 @@ def test_dither_paper_example_exhaustive(oracle):
     assert Fraction(n_high, TWO32) == p_high
 
 
+def round_half_even(fr):
+    """Nearest integer to a Fraction, ties to the even one."""
+    fl = math.floor(fr)
+    rem = fr - fl
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+        return fl + 1
+    return fl
+
+
 def test_dither_probabilities_match_definition(oracle):
-    """xi(y) = l_high w.p. (y - l_low)/(l_high - l_low) (Def. 3), exactly above the lowest
-    level and up to the 2^-32 truncation below it; hence E xi(y) = y."""
+    """xi(y) = l_high w.p. (y - l_low)/(l_high - l_low) (Def. 3): exactly above the lowest level;
+    below it to 23 bits, rounded to nearest (ties to even), so within 2^-24; hence E xi(y) = y
+    up to 2^-24 of the level spacing.  Subnormal y included."""
     rng = np.random.default_rng(31)
-    for s in (1, 2, 3, 4, 8, 16, 40, 126, 127):
-        ys = np.concatenate([rng.uniform(0, 1, 40), np.exp2(-rng.uniform(0, 60, 40)), [1.0, 0.5, 2.0 ** (1 - min(s, 100))]])
+    TWO23 = 1 << 23
+    for s in (1, 2, 3, 4, 8, 16, 40, 100, 120, 126, 127):
+        ys = np.concatenate([rng.uniform(0, 1, 40), np.exp2(-rng.uniform(0, 60, 40)), np.exp2(-rng.uniform(90, 149, 30)),
+                             [1.0, 0.5, 2.0 ** (1 - min(s, 100)), 1e-45, 1.1754942e-38]])
         for y in ys.astype(np.float32):
             yb = f32_bits(y)
             fy = Fraction(float(y))
@@ -390,15 +402,61 @@ def test_dither_probabilities_match_definition(oracle):
             l_lo, l_hi = level_value(s, c_lo), level_value(s, c_lo + 1)
             assert l_lo <= fy < l_hi
             p_exact = (fy - l_lo) / (l_hi - l_lo)
+            assert T % 512 == 0                      # only the top 23 bits of the word decide
             if c_lo >= 1:
                 assert Fraction(T, TWO32) == p_exact
             else:
-                assert T == math.floor(p_exact * TWO32)
+                assert T // 512 == round_half_even(p_exact * TWO23)
+                assert abs(Fraction(T, TWO32) - p_exact) <= Fraction(1, 2 * TWO23)
             mean = l_lo + Fraction(T, TWO32) * (l_hi - l_lo)
-            assert abs(mean - fy) <= Fraction(1, TWO32) * l_hi
-    # y >= 1 is level 1, zero and subnormal y are level 0
+            assert abs(mean - fy) <= Fraction(1, 2 * TWO23) * l_hi
+    # y >= 1 is level 1, zero is level 0; a subnormal y is far below 2^-23 of the lowest level unless s is
+    # close to 127, where it is coded like any other value: P(2^-126) = y 2^126 exactly for s = 127
     assert oracle.dither_level(0x3F800001, 4, 0) == 4
     assert oracle.dither_level(0, 4, 0) == 0 and oracle.dither_level(0x007FFFFF, 4, 0) == 0
+    assert dither_threshold(oracle, 0x00400000, 127) == (0, (1 << 22) << 9)
+    assert dither_threshold(oracle, 0x00000001, 127) == (0, 1 << 9)
+
+
+def test_dither_low_region_by_exhaustion(oracle):
+    """All 2^32 words for values below the lowest level: the count of "up" outcomes is the 23-bit
+    threshold times 2^9, i.e. P(up) = round(y 2^(s+22)) / 2^23 (Def. 3's (y - 0) / (2^(1-s) - 0) to 23 bits)."""
+    TWO23 = 1 << 23
+    for s, y in [(8, 0.003), (4, 0.1), (120, 2.0 ** -125 * 1.3), (127, 1e-39)]:
+        yb = f32_bits(np.float32(y))
+        fy = Fraction(float(np.float32(y)))
+        assert fy < Fraction(2) ** (1 - s)
+        want = round_half_even(fy * Fraction(2) ** (s + 22))
+        assert 0 < want < TWO23
+        assert oracle.dither_count(yb, s, 1) == want * 512
+        assert oracle.dither_count(yb, s, 0) == TWO32 - want * 512
+
+
+def test_dithering_words(oracle):
+    """The dithering stream: one Philox call per 8 elements, counter (g/8, worker, 1); each element's word is a
+    rearrangement of 32 distinct bits of the call's output, so it is uniform whenever the call's output is:
+    every one of its 32 source bits moves exactly one distinct bit of the word, the other 96 bits none."""
+    for j in range(8):
+        base = oracle.dither_word_of_call([0, 0, 0, 0], j)
+        assert base == 0
+        moved = []
+        for word in range(4):
+            for bit in range(32):
+                w = [0, 0, 0, 0]
+                w[word] = 1 << bit
+                moved.append(oracle.dither_word_of_call(w, j))
+        used = [m for m in moved if m]
+        assert len(used) == 32 and all(bin(m).count("1") == 1 for m in used) and len(set(used)) == 32
+        # elements 0..3 read words 0 and 1 only, elements 4..7 words 2 and 3 only
+        assert all(m == 0 for i, m in enumerate(moved) if (i // 64) != (j // 4))
+    # elements 0 and 1 (4 and 5) take a word each, as it is
+    w = [0x01234567, 0x89ABCDEF, 0x0F1E2D3C, 0x4B5A6978]
+    assert [oracle.dither_word_of_call(w, j) for j in (0, 1, 4, 5)] == w
+    assert oracle.dither_word_of_call(w, 2) == 0x456789AB and oracle.dither_word_of_call(w, 3) == 0xCDEF0123
+    # keying: counter (lo32(g/8), hi32(g/8), worker, 1), key = (lo32(seed), hi32(seed))
+    for seed, worker, g in [(0, 0, 0), (5, 3, 7), (2**40 + 9, 7, 8), (11, 2, 2**35 + 13), (1, 65535, 2**36 - 1)]:
+        call = oracle.philox4x32_10([(g >> 3) & 0xFFFFFFFF, g >> 35, worker, 1], [seed & 0xFFFFFFFF, seed >> 32])
+        assert oracle.dither_word(seed, worker, g) == oracle.dither_word_of_call(call, g & 7)
 
 
 def test_dithering_tends_to_natural_compression(oracle):
