@@ -177,10 +177,9 @@ __device__ __forceinline__ float inv_of_norm(float norm) {
 // Parameters that depend on s only.
 struct LevelParams {
     uint32_t s;
-    int32_t e_min;        // 128 - s: smallest exponent field of y in the geometric region
+    int32_t e_base;       // 127 - s: exponent field of 2^-s, one below that of the lowest non-zero level
     int32_t e_max;        // 127: exponent field of y = 1, the top level
-    uint32_t regular_lo;  // (128 - s) << 23: bits of the lowest non-zero level 2^(1-s)
-    float low_scale;      // 2^(s+31): y * low_scale = threshold of the linear region (s <= 95)
+    float half_lowest;    // 2^-s (s <= 95)
     uint32_t standard;    // 1: standard dithering (levels j/s) instead of the natural level set
     float s_float;        // s as a float (standard dithering)
 };
@@ -189,47 +188,51 @@ __device__ __forceinline__ LevelParams level_params(uint32_t s, uint32_t standar
     p.s = s;
     p.standard = standard;
     p.s_float = (float)s;
-    p.e_min = 128 - (int32_t)s;
+    p.e_base = 127 - (int32_t)s;
     p.e_max = 127;
-    p.regular_lo = (uint32_t)(128 - s) << 23;
-    p.low_scale = (s <= 95 && !standard) ? bits_f32((uint32_t)(127 + s + 31) << 23) : 0.0f;
+    p.half_lowest = (s <= 95 && !standard) ? bits_f32((uint32_t)(127 - s) << 23) : 0.0f;
     return p;
 }
 
-// Level code of y = fl(|x| * inv) given the COMPLEMENT rc of the element's random word r.
-// y = 2^-k (1 + m): for y >= 2^(1-s) the code is s - k, plus one with probability m
-// (r < m 2^9); below 2^(1-s) it is 1 with probability y 2^(s-1) (r < floor(y 2^(s+31)))
-// and 0 otherwise; y >= 1 gives s.
+// Level code of y = fl(|x| * inv) given the COMPLEMENT rc of the element's random word r, of
+// which the top 23 bits r23 decide.  y = 2^-k (1 + m): for y >= 2^(1-s) the code is s - k, plus
+// one with probability m (r23 < m 2^23); below 2^(1-s) it is 1 with probability y 2^(s-1) taken
+// to 23 bits (r23 < round(y 2^(s+22)), ties to even) and 0 otherwise; y >= 1 gives s.
 //
-// SMALL_S (s <= 95), branch-free: adding the 23 complemented top bits of r to y's bits
-// carries into the exponent field exactly when r < m 2^9; the exponent, clamped to
-// [128-s, 127] and rebased, is the code minus one in the geometric region and 0 below it.
-// The last unit is "geometric region, or r < T" where T = floor(y 2^(s+31)) comes from one
-// multiply and a truncating conversion, and r < T is the carry of T + ~r.
+// SMALL_S (s <= 95), branch-free.  Below the lowest level, z = fl(y/2 + 2^-s) -- one fused
+// multiply-add -- lies in [2^-s, 2^(1-s)] and its mantissa field is exactly that 23-bit
+// threshold, so both regions become one rule on w = max(y, z) (z <= y from 2^(1-s) on): adding
+// the 23 complemented top bits of r to w's bits carries into the exponent field exactly when
+// r23 is below w's mantissa, and the exponent field, clamped to [127-s, 127] and rebased, is
+// the code.
 template <bool SMALL_S>
 __device__ __forceinline__ uint32_t dither_level(float x, float inv, uint32_t rc, const LevelParams& lp) {
     const float y = fabsf(x) * inv;
-    const uint32_t yb = f32_bits(y);
     if (SMALL_S) {
-        const uint32_t bumped = yb + (rc >> 9);
-        int32_t e_clamped;  // exponent after the bump, clamped to [e_min, e_min + s - 1]
-        asm("v_med3_i32 %0, %1, %2, %3" : "=v"(e_clamped) : "v"(bumped >> 23), "v"(lp.e_min), "v"(lp.e_max));
-        uint32_t T;
-        asm("v_cvt_u32_f32 %0, %1" : "=v"(T) : "v"(y * lp.low_scale));  // truncates; saturates out of range
-        uint32_t unused;
-        const bool below = __builtin_uadd_overflow(T, rc, &unused);  // T + ~r carries  <=>  r < T
-        const bool geometric = yb >= lp.regular_lo;
-        return (uint32_t)(e_clamped - lp.e_min) + ((below || geometric) ? 1u : 0u);
+        const float w = fmaxf(y, __builtin_fmaf(y, 0.5f, lp.half_lowest));
+        const uint32_t bumped = f32_bits(w) + (rc >> 9);
+        int32_t e_clamped;
+        asm("v_med3_i32 %0, %1, %2, %3" : "=v"(e_clamped) : "v"(bumped >> 23), "v"(lp.e_base), "v"(lp.e_max));
+        return (uint32_t)(e_clamped - lp.e_base);
     } else {
-        const uint32_t ybm = yb & 0x7FFFFFFFu;
-        const uint32_t r = ~rc;
+        const uint32_t ybm = f32_bits(y) & 0x7FFFFFFFu;
+        const uint32_t r23 = ~rc >> 9;
         const uint32_t e_y = ybm >> 23, m = ybm & 0x7FFFFFu;
         if (ybm >= 0x3F800000u) return lp.s;
-        if (e_y == 0) return 0;
-        if ((int32_t)e_y >= lp.e_min) return e_y - (127u - lp.s) + (r < (m << 9) ? 1u : 0u);
-        const uint32_t sh = 127u - lp.s - e_y;  // threshold = (2^31 | m 2^8) >> sh
-        const uint32_t T = sh >= 32 ? 0u : ((0x80000000u | (m << 8)) >> sh);
-        return r < T ? 1u : 0u;
+        if (e_y + lp.s >= 128u) return e_y - (127u - lp.s) + (r23 < m ? 1u : 0u);
+        // y 2^(s+22) = M / 2^sh with M the 24-bit significand (no hidden bit for a subnormal y)
+        const uint32_t M = e_y ? (0x800000u | m) : m;
+        const uint32_t sh = 128u - lp.s - (e_y ? e_y : 1u);
+        uint32_t T;
+        if (sh == 0) {
+            T = M;
+        } else if (sh > 25) {
+            T = 0;
+        } else {
+            const uint32_t q = M >> sh, rem = M & ((1u << sh) - 1u), half = 1u << (sh - 1);
+            T = q + ((rem > half || (rem == half && (q & 1u))) ? 1u : 0u);
+        }
+        return r23 < T ? 1u : 0u;
     }
 }
 
@@ -300,23 +303,68 @@ __device__ __forceinline__ void load8(const float* __restrict__ x, uint64_t i0, 
     }
 }
 
+// The dithering stream: one Philox call per 8 consecutive elements, counter (g/8, worker, 1).
+// Elements 0..3 of the group share (a, b) = (w0, w1), elements 4..7 (a, b) = (w2, w3); the four
+// elements of such a half take a, b, a<<16 | b>>16 and b<<16 | a>>16: each a rearrangement of
+// 32 distinct bits of the call's output, so uniform by itself, which is all that unbiasedness
+// and the second-moment bound of the operator need (they are sums over coordinates).
+// Complementing commutes with the rearrangement, so the kernels draw complemented calls.
+__device__ __forceinline__ void dither_half_words(uint32_t a, uint32_t b, uint32_t rc[4]) {
+    rc[0] = a;
+    rc[1] = b;
+    rc[2] = __builtin_amdgcn_alignbit(a, b, 16);
+    rc[3] = __builtin_amdgcn_alignbit(b, a, 16);
+}
+// Complemented words of the 8 elements of group `call` (global elements 8 call .. 8 call + 7).
+__device__ __forceinline__ void dither_group_words(uint64_t call, uint32_t worker, uint32_t k0, uint32_t k1,
+                                                   uint32_t rc[8]) {
+    uint32_t w[4];
+    philox4x32_10<true>((uint32_t)call, (uint32_t)(call >> 32), worker, kDomainDither, k0, k1, w);
+    dither_half_words(w[0], w[1], rc);
+    dither_half_words(w[2], w[3], rc + 4);
+}
+// Complemented words of the quad with global quad index gq (global elements 4 gq .. 4 gq + 3).
+__device__ __forceinline__ void dither_quad_words(uint64_t gq, uint32_t worker, uint32_t k0, uint32_t k1,
+                                                  uint32_t rc[4]) {
+    uint32_t w[4];
+    philox4x32_10<true>((uint32_t)(gq >> 1), (uint32_t)(gq >> 33), worker, kDomainDither, k0, k1, w);
+    const bool upper = gq & 1u;
+    dither_half_words(upper ? w[2] : w[0], upper ? w[3] : w[1], rc);
+}
+// The same for two quads per lane at one call per lane.  Contract: all 64 lanes call; lane l and
+// lane l ^ 1 hold the two quads of one group, in both rounds (global quad indices gq_a and gq_b
+// of the lane: gq_x even in even lanes, and lane l ^ 1 holds gq_x ^ 1).  Even lanes then draw the
+// call of round a, odd lanes the call of round b, and adjacent lanes exchange halves.
+__device__ __forceinline__ void dither_quad_words_two_rounds(uint64_t gq_a, uint64_t gq_b, uint32_t worker,
+                                                             uint32_t k0, uint32_t k1, uint32_t rc_a[4],
+                                                             uint32_t rc_b[4]) {
+    const bool odd = gq_a & 1u;
+    const uint64_t call = (odd ? gq_b : gq_a) >> 1;
+    uint32_t w[4], o[4];
+    philox4x32_10<true>((uint32_t)call, (uint32_t)(call >> 32), worker, kDomainDither, k0, k1, w);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = __builtin_amdgcn_update_dpp(0u, w[i], 0xB1, 0xF, 0xF, true);  // lane l ^ 1's word
+    dither_half_words(odd ? o[2] : w[0], odd ? o[3] : w[1], rc_a);  // round a: the even lane's call
+    dither_half_words(odd ? w[2] : o[0], odd ? w[3] : o[1], rc_b);  // round b: the odd lane's call
+}
+
 // Complemented random words of the 8 elements with global indices g0 .. g0+7.
 template <bool FAST>
 __device__ __forceinline__ void words8(uint64_t g0, uint32_t worker, uint32_t k0, uint32_t k1, uint32_t rc[8]) {
-    if (FAST) {  // g0 is a multiple of 4: two whole calls
-        random_words4<true>(g0 >> 2, worker, kDomainDither, k0, k1, rc);
-        random_words4<true>((g0 >> 2) + 1, worker, kDomainDither, k0, k1, rc + 4);
-    } else {     // three calls cover any alignment
-        uint32_t w[12];
-        random_words4<true>(g0 >> 2, worker, kDomainDither, k0, k1, w);
-        random_words4<true>((g0 >> 2) + 1, worker, kDomainDither, k0, k1, w + 4);
-        random_words4<true>((g0 >> 2) + 2, worker, kDomainDither, k0, k1, w + 8);
-        const uint32_t o = (uint32_t)g0 & 3u;
+    const uint32_t o = (uint32_t)g0 & 7u;
+    if (FAST && o == 0) {  // one whole group
+        dither_group_words(g0 >> 3, worker, k0, k1, rc);
+        return;
+    }
+    uint32_t w[16];  // two groups cover any alignment
+    dither_group_words(g0 >> 3, worker, k0, k1, w);
+    dither_group_words((g0 >> 3) + 1, worker, k0, k1, w + 8);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t a = w[j], b = w[j + 1], c = w[j + 2], d = w[j + 3];
-            rc[j] = o == 0 ? a : o == 1 ? b : o == 2 ? c : d;
-        }
+    for (int j = 0; j < 8; ++j) {
+        uint32_t r = w[j];
+#pragma unroll
+        for (int sh = 1; sh < 8; ++sh) r = o == (uint32_t)sh ? w[j + sh] : r;
+        rc[j] = r;
     }
 }
 
@@ -369,7 +417,7 @@ __device__ __forceinline__ uint32_t sign_nibble4(u32x4 v) {
 
 // Encodes quad q of the workgroup's tile and stores its codes; code_base / sign_base point
 // at the tile's first code / sign word (workgroup-uniform, so q stays a 32-bit offset) and
-// g_quad is the quad's global index in the random stream.  Must be called by all 64 lanes
+// rc holds the complemented random words of its four elements.  Must be called by all 64 lanes
 // of a wavefront with consecutive q (lane l holds q0 + l, q0 a multiple of 8); `in` says
 // whether the lane's quad exists and is the same for each run of 8 lanes.  Stores: nibble formats, one word of
 // 8 codes from every even lane; byte format, one word of 4 codes from every lane; sign
@@ -377,10 +425,9 @@ __device__ __forceinline__ uint32_t sign_nibble4(u32x4 v) {
 template <int FMT>
 __device__ __forceinline__ void encode_store_quad(const DitherEncodeArgs& a, const LevelParams& lp, u32x4 v,
                                                   const float inv[4], uint32_t* __restrict__ code_base,
-                                                  uint32_t* __restrict__ sign_base, uint32_t q, uint64_t g_quad,
+                                                  uint32_t* __restrict__ sign_base, uint32_t q, const uint32_t rc[4],
                                                   bool in) {
-    uint32_t rc[4], c[4];
-    random_words4<true>(g_quad, a.worker, kDomainDither, a.k0, a.k1, rc);
+    uint32_t c[4];
     levels4(v, inv, rc, lp, c);
     if (FMT == kFmtByte) {
         const uint32_t w = c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24);
@@ -395,6 +442,19 @@ __device__ __forceinline__ void encode_store_quad(const DitherEncodeArgs& a, con
     if (FMT != kFmtFused) {
         const uint32_t packed = gather_nibbles8(sign_nibble4(v));
         if (in && (threadIdx.x & 7) == 0) store_stream(sign_base + (q >> 3), packed);
+    }
+}
+
+// Words of the lane's quads q_a and q_b (tile-local; q_global is the tile's first quad in the
+// random stream).  When q_global is even -- lanes then hold the two quads of a group side by
+// side -- one call per lane serves both rounds; otherwise every quad draws the call it lies in.
+__device__ __forceinline__ void tile_quad_words(const DitherEncodeArgs& a, uint64_t q_global, uint32_t q_a, uint32_t q_b,
+                                                uint32_t rc_a[4], uint32_t rc_b[4]) {
+    if ((q_global & 1u) == 0) {  // wave-uniform
+        dither_quad_words_two_rounds(q_global + q_a, q_global + q_b, a.worker, a.k0, a.k1, rc_a, rc_b);
+    } else {
+        dither_quad_words(q_global + q_a, a.worker, a.k0, a.k1, rc_a);
+        dither_quad_words(q_global + q_b, a.worker, a.k0, a.k1, rc_b);
     }
 }
 
@@ -455,12 +515,25 @@ void dither_bucket_encode_vec_kernel(DitherEncodeArgs a) {
     const uint64_t q_global = (a.index_offset + begin) >> 2;
     uint32_t* __restrict__ code_base = reinterpret_cast<uint32_t*>(a.code_out + (FMT == kFmtByte ? begin : begin >> 1));
     uint32_t* __restrict__ sign_base = reinterpret_cast<uint32_t*>(a.sign_out + (begin >> 3));
+    if (QPL == 1) {
+        uint32_t rc[4];
+        dither_quad_words(q_global + threadIdx.x, a.worker, a.k0, a.k1, rc);
+        encode_store_quad<FMT>(a, lp, v[0], iv4, code_base, sign_base, threadIdx.x, rc, threadIdx.x < vec_quads);
+    } else {
 #pragma unroll
-    for (int k = 0; k < QPL; ++k) {
-        const uint32_t q = threadIdx.x + k * kBlock;
-        if (k * kBlock < vec_quads)  // block-uniform: skip rounds no lane takes part in
-            encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, q_global + q, q < vec_quads);
-        __builtin_amdgcn_sched_barrier(0);  // one quad at a time keeps the register count low
+        for (int k = 0; k + 1 < QPL; k += 2) {
+            const uint32_t q = threadIdx.x + k * kBlock;
+            if (k * kBlock < vec_quads) {  // block-uniform: skip rounds no lane takes part in
+                uint32_t rc_a[4], rc_b[4];
+                tile_quad_words(a, q_global, q, q + kBlock, rc_a, rc_b);
+                encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, rc_a, q < vec_quads);
+                __builtin_amdgcn_sched_barrier(0);  // one quad at a time keeps the register count low
+                if ((k + 1) * kBlock < vec_quads)
+                    encode_store_quad<FMT>(a, lp, v[k + 1], iv4, code_base, sign_base, q + kBlock, rc_b,
+                                           q + kBlock < vec_quads);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
     if (tail0 < len && threadIdx.x < 4 && tail0 + threadIdx.x * 8 < len) {
         const uint32_t l0 = tail0 + threadIdx.x * 8;
@@ -554,11 +627,21 @@ void dither_multi_bucket_encode_kernel(DitherEncodeArgs a, uint32_t log2_l, uint
     uint32_t* __restrict__ code_base =
         reinterpret_cast<uint32_t*>(a.code_out + (FMT == kFmtByte ? tile_elem0 : tile_elem0 >> 1));
     uint32_t* __restrict__ sign_base = reinterpret_cast<uint32_t*>(a.sign_out + (tile_elem0 >> 3));
+    if (QPL == 1) {
+        uint32_t rc[4];
+        dither_quad_words(q_global + q_first, a.worker, a.k0, a.k1, rc);
+        encode_store_quad<FMT>(a, lp, v[0], iv4, code_base, sign_base, q_first, rc, in[0]);
+    } else {
 #pragma unroll
-    for (int k = 0; k < QPL; ++k) {
-        const uint32_t q = q_first + k * lanes;
-        encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, q_global + q, in[k]);
-        __builtin_amdgcn_sched_barrier(0);  // one quad at a time keeps the register count low
+        for (int k = 0; k + 1 < QPL; k += 2) {
+            const uint32_t q = q_first + k * lanes;
+            uint32_t rc_a[4], rc_b[4];
+            tile_quad_words(a, q_global, q, q + lanes, rc_a, rc_b);
+            encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, rc_a, in[k]);
+            __builtin_amdgcn_sched_barrier(0);  // one quad at a time keeps the register count low
+            encode_store_quad<FMT>(a, lp, v[k + 1], iv4, code_base, sign_base, q + lanes, rc_b, in[k + 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
     // the ragged last bucket (fewer than `bucket` <= 2048 elements) is the last workgroup's second job
     if (blockIdx.x == gridDim.x - 1 && full_buckets * a.segs.bucket < a.segs.d)
@@ -754,6 +837,8 @@ __global__ __launch_bounds__(kBlock) void dither_segment_encode_kernel(DitherEnc
             uint32_t* __restrict__ code_base =
                 reinterpret_cast<uint32_t*>(a.code_out + (FMT == kFmtByte ? cb : cb >> 1));
             uint32_t* __restrict__ sign_base = reinterpret_cast<uint32_t*>(a.sign_out + (cb >> 3));
+            uint32_t rc[2][4];
+            tile_quad_words(a, q_global, threadIdx.x, threadIdx.x + kBlock, rc[0], rc[1]);
             if (one_segment) {
                 const float iv = hit.aux;
                 const float iv4[4] = {iv, iv, iv, iv};
@@ -761,9 +846,10 @@ __global__ __launch_bounds__(kBlock) void dither_segment_encode_kernel(DitherEnc
                 for (int k = 0; k < 2; ++k) {
                     const uint32_t q = threadIdx.x + k * kBlock;
                     if (k * kBlock < vec_quads)
-                        encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, q_global + q, q < vec_quads);
+                        encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, rc[k], q < vec_quads);
                 }
             } else {  // each element takes the reciprocal norm of its own segment
+#pragma unroll
                 for (int k = 0; k < 2; ++k) {
                     const uint32_t q = threadIdx.x + k * kBlock;
                     if (k * kBlock < vec_quads) {
@@ -775,7 +861,7 @@ __global__ __launch_bounds__(kBlock) void dither_segment_encode_kernel(DitherEnc
                             if (cursor_advance(cur, bnd, nb, q * 4 + j)) iv = a.inv_norm[s0 + cur.idx];
                             iv4[j] = iv;
                         }
-                        encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, q_global + q, q < vec_quads);
+                        encode_store_quad<FMT>(a, lp, v[k], iv4, code_base, sign_base, q, rc[k], q < vec_quads);
                     }
                 }
             }

@@ -230,7 +230,7 @@ def test_dithering_reduces_to_natural_compression_on_gpu(nc, oracle):
         e = (int(u[i]) >> 23) & 255
         if e < 2:
             continue
-        r = oracle.random_word(5, 0, oracle.DOMAIN_DITHER, i)
+        r = oracle.dither_word(5, 0, i)
         assert int(code[i]) - 126 == oracle.nat_round(int(u[i]), r) - 127
 
 
@@ -423,24 +423,25 @@ def test_decoding_from_8_bit_norms(nc, oracle, wl, s, bucket, n):
 @pytest.mark.parametrize("s", [4, 8, 100])
 def test_words_at_the_threshold(nc, oracle, s):
     """Inputs built from the random words (max-norm 1, so y = |x|): in the geometric region a
-    mantissa equal to the top 23 bits of the element's word stays and one more goes up; below the
-    lowest level y = r 2^-(s+31) has threshold r (stays at 0) and (r + 256) 2^-(s+31) goes to the
-    lowest level.  Whole vector in one segment (two-pass path) and bucketed (one-pass path)."""
+    mantissa equal to the top 23 bits r23 of the element's word stays and one more goes up; below
+    the lowest level y = r23 2^-(s+22) has threshold r23 (stays at 0) and (r23 + 1) 2^-(s+22) goes
+    to the lowest level.  Whole vector in one segment (two-pass path) and bucketed (one-pass path)."""
     d, seed, worker, off = 3 * 8192, 31, 2, 8
     rng = np.random.default_rng(2)
-    r = np.array([oracle.random_word(seed, worker, oracle.DOMAIN_DITHER, off + i) for i in range(d)], np.uint64)
+    r = np.array([oracle.dither_word(seed, worker, off + i) for i in range(d)], np.uint64)
     sign = rng.integers(0, 2, d).astype(np.uint32)
     k = rng.integers(1, s, d).astype(np.uint32)                 # y in [2^-k, 2^(1-k)), 1 <= k <= s-1
     m_stay = (r >> np.uint64(9)).astype(np.uint32)
-    linear = ((r & np.uint64(255)) == 0) & (r > 0)              # words with at most 24 significant bits
+    linear = (rng.integers(0, 8, d) == 0) & (m_stay > 0) & (m_stay < (1 << 23) - 1)
     linear[::512] = False                                       # (these positions hold the buckets' maxima)
-    assert linear.sum() > 20
+    assert linear.sum() > 1000
     for bump, up in [(0, 0), (1, 1)]:
         ok = m_stay + bump < (1 << 23)
         m = np.where(ok, m_stay + bump, m_stay)
         x = ((sign << 31) | ((127 - k) << 23) | m).astype(np.uint32).view(np.float32)
-        t = (r[linear] + np.uint64(256 * bump)).astype(np.float64)
-        x[linear] = (np.ldexp(t, -(s + 31)) * np.where(sign[linear] == 1, -1.0, 1.0)).astype(np.float32)
+        t = (m_stay[linear] + bump).astype(np.float64)
+        x[linear] = (np.ldexp(t, -(s + 22)) * np.where(sign[linear] == 1, -1.0, 1.0)).astype(np.float32)
+        assert np.array_equal(np.abs(x[linear]).astype(np.float64), np.ldexp(t, -(s + 22)))     # exact
         x[::512] = 1.0                                           # every bucket's max-norm is 1
         expect = (s - k + up).astype(np.int64)
         expect[linear] = up

@@ -111,7 +111,7 @@ def test_words_at_the_threshold(nc, oracle, s):
     (the element's own word: stays at level j), 512 more units go up.  Only words that are a
     multiple of 2^9 fit a binary32 fraction for j = 1."""
     d, seed, worker, off = 4 * 8192, 41, 1, 4
-    r = np.array([oracle.random_word(seed, worker, 1, off + i) for i in range(d)], np.uint64)
+    r = np.array([oracle.dither_word(seed, worker, off + i) for i in range(d)], np.uint64)
     pick = ((r & np.uint64(511)) == 0) & (r > 0) & (r < (1 << 32) - 512)
     pick[::512] = False
     assert pick.sum() > 20
