@@ -129,7 +129,7 @@ __device__ __forceinline__ NormAcc norm_zero() { return NormAcc{0.0, 0.0f}; }
 __device__ __forceinline__ void norm_add(NormAcc& a, float x, int pnorm) {
     if (pnorm == kNormInf) a.mx = fmaxf(a.mx, fabsf(x));
     else if (pnorm == kNormL1) a.sum += (double)fabsf(x);
-    else a.sum += (double)x * (double)x;
+    else a.sum = __builtin_fma((double)x, (double)x, a.sum);  // (the square of a binary32 value is exact in double)
 }
 __device__ __forceinline__ NormAcc norm_merge(NormAcc a, NormAcc b, int pnorm) {
     if (pnorm == kNormInf) a.mx = fmaxf(a.mx, b.mx); else a.sum += b.sum;
