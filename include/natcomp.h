@@ -15,8 +15,14 @@
  *   - Randomness: element i of a call uses the 32-bit word of global index
  *     g = index_offset + i of the stream (seed, worker, operator): output word (g mod 4)
  *     of Philox-4x32-10 with key = (lo32(seed), hi32(seed)) and counter =
- *     (lo32(g/4), hi32(g/4), worker, domain), domain 0 for C_nat, 1 for D_nat, 2 for the
- *     sparsifier's index selection, 3 for the master's C_nat and 4 for compressed norms.
+ *     (lo32(g/4), hi32(g/4), worker, domain), domain 0 for C_nat, 2 for the sparsifier's
+ *     index selection, 3 for the master's C_nat and 4 for compressed norms.
+ *     The dithering operators (domain 1) draw one call per 8 elements instead: counter
+ *     (lo32(g/8), hi32(g/8), worker, 1); with (a, b) = output words (0, 1) for g mod 8 < 4 and
+ *     (2, 3) otherwise, the element's word is a, b, a<<16 | b>>16 or b<<16 | a>>16 for
+ *     g mod 4 = 0, 1, 2, 3: each a rearrangement of 32 distinct bits of the call's output, so
+ *     uniform by itself (neighbouring elements are not independent; unbiasedness and the
+ *     variance bound of the operators are statements about single coordinates).
  *     Results therefore do not depend on how a vector is split into calls or launches.
  *
  * Plane layouts (little-endian bit order inside a byte):
@@ -114,8 +120,12 @@ nc_status nc_nat_decode(const uint8_t *exp, const uint8_t *sign, uint64_t d, flo
  *   seg_offsets == NULL, bucket == 0: one segment.
  * Per element: y = fl(|x_i| * fl(1/norm)) in binary32; y between adjacent levels
  * l_low <= y <= l_high goes to l_high with probability (y - l_low)/(l_high - l_low), decided
- * by an integer comparison of the random word with a threshold built from y's bits; y >= 1
- * is the level 1.  A segment whose norm is below 2^-126 (zero included) codes to zeros.
+ * by an integer comparison of the top 23 bits r23 of the random word with a 23-bit threshold
+ * built from y's bits: for y = 2^-k (1 + m/2^23) >= 2^(1-s) the threshold is m (exact); below
+ * the lowest level 2^(1-s) it is y 2^(s+22) rounded to the nearest integer, ties to even
+ * (within 2^-24 of the exact probability; for s <= 126 the mantissa field of
+ * fl(y/2 + 2^-s)); y >= 1 is the level 1.  A segment whose norm is below 2^-126 (zero
+ * included) codes to zeros.
  *
  *   p           1, 2 or INFINITY.               s  number of levels, 1..127.
  *   norms_out   DEVICE, one float per segment: the p-norm (sum accumulated in double,
