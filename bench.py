@@ -10,7 +10,9 @@ batched encoder), a `roofline_aggregate` object for the fused sum (also on rotat
 sets) and a `cpu_baseline` object (the CPU oracle timed on the host cores).
 
 Timing rules: HIP events on the launch stream around every kernel of every timed step (of
-every k-th step when there are more than 64); median, minimum and mean are reported.  Before
+every k-th step when there are more than 64); median, minimum and mean are reported.  Kernels
+timed on their own (the cold aggregate, the other configurations) take one event pair per four
+consecutive launches, which spreads the 3 to 4 us the markers cost over the group.  Before
 the warm-up steps the same step is run for a fixed wall time (`settle_ms`, its step count is
 printed as `settle_steps`) so that the clocks have left their idle state; the timed region is
 still exactly `--steps` steps after `--warmup` further untimed ones.  Kernels whose working
@@ -56,28 +58,38 @@ def sets_for(working_set_bytes):
 class Timer:
     """HIP-event timing of launches on torch's current stream."""
 
-    def __init__(self, torch, np):
-        self.torch, self.np = torch, np
+    def __init__(self, torch, np, warm_ms=25.0):
+        # warm_ms: a kernel is run for this long before it is timed; after a change of workload the clocks
+        # take some 10 ms to settle (the first launches are fast, the next few dozen up to 30 % slower)
+        self.torch, self.np, self.warm_ms = torch, np, warm_ms
 
     def stats(self, samples_ms):
         a = self.np.asarray(samples_ms, dtype=self.np.float64)
         return {"median": float(self.np.median(a)), "min": float(a.min()), "mean": float(a.mean()), "samples": int(a.size),
                 "raw": [float(v) for v in a]}
 
-    def rotating(self, fns, reps=20, warm=5):
-        """fns[i % len(fns)]() is one launch (or group of launches) on buffer set i; every call is
-        bracketed by two events.  Returns the statistics in ms."""
+    def rotating(self, fns, reps=20, warm=5, group=4):
+        """fns[i % len(fns)]() is one launch (or group of launches) on buffer set i.  A sample is the
+        time between two events around `group` consecutive calls (on consecutive buffer sets), divided
+        by `group`: the cost of the event markers themselves, 3 to 4 us per pair, is spread over the
+        group.  Returns the statistics over `reps` samples, in ms per call."""
         torch = self.torch
-        for i in range(warm):
-            fns[i % len(fns)]()
-        torch.cuda.synchronize()
+        t0, i = time.perf_counter(), 0
+        while i < max(warm, group) or (time.perf_counter() - t0) * 1e3 < self.warm_ms:   # at least `warm` calls and warm_ms
+            for _ in range(4):
+                fns[i % len(fns)]()
+                i += 1
+            torch.cuda.synchronize()
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        for i, (a, b) in enumerate(evs):
+        call = 0
+        for a, b in evs:
             a.record()
-            fns[(warm + i) % len(fns)]()
+            for _ in range(group):
+                fns[call % len(fns)]()
+                call += 1
             b.record()
         torch.cuda.synchronize()
-        return self.stats([a.elapsed_time(b) for a, b in evs])
+        return self.stats([a.elapsed_time(b) / group for a, b in evs])
 
 
 def _entry(st, alg_bytes, input_bytes, note, nsets):
@@ -236,7 +248,7 @@ def secondary_kernels(nc, wl, torch, np, timer):
         for w in range(n):
             nc.dither_encode(x4[w], math.inf, 4, 0, worker=w, bucket=bucket, norms_out=norms4[w], code_out=code4[w])
 
-    st = timer.rotating([encode_all], reps=20, warm=3)
+    st = timer.rotating([encode_all], reps=20, warm=3, group=1)
     res["config4_dither_inf_4_bucket_encode_x8"] = _entry(st, 4.5 * d4 * n, 4.0 * d4 * n,
                                                          "8 one-pass launches over 4.4 GB of input; 4 + 0.5 B per element", 1)
     st = timer.rotating([lambda: nc.aggregate_sum(nc.NC_KIND_DITHER, d4, code4, None, norms4, s=4, bucket=bucket, out=out4)],
