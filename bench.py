@@ -122,32 +122,36 @@ class Probe:
 
     def ceilings(self, timer, nbytes=1 << 29):
         """GB/s of a streaming copy / read / fill / 9:4 mix over buffers of `nbytes` (rotated over
-        two sets, far beyond the last-level cache), and Philox calls per second."""
+        enough sets to move more than 600 MB before one comes round again, far beyond the
+        last-level cache), and Philox calls per second."""
         torch, L = self.torch, self.L
-        a = [torch.zeros(nbytes // 4, dtype=torch.int32, device="cuda") for _ in range(2)]
-        b = [torch.ones(nbytes // 4, dtype=torch.int32, device="cuda") for _ in range(2)]
-        c = [torch.ones(nbytes // 16, dtype=torch.int32, device="cuda") for _ in range(2)]
-        dst = [torch.empty(nbytes // 4, dtype=torch.int32, device="cuda") for _ in range(2)]
+        nsets = max(2, -(-600_000_000 // nbytes))
+        R = range(nsets)
+        a = [torch.zeros(nbytes // 4, dtype=torch.int32, device="cuda") for _ in R]
+        b = [torch.ones(nbytes // 4, dtype=torch.int32, device="cuda") for _ in R]
+        c = [torch.ones(nbytes // 16, dtype=torch.int32, device="cuda") for _ in R]
+        dst = [torch.empty(nbytes // 4, dtype=torch.int32, device="cuda") for _ in R]
         sink = torch.zeros(1024, dtype=torch.int32, device="cuda")
 
         def ok(rc):
             assert rc == 0, f"probe launch failed: {rc}"
 
         res = {}
-        st = timer.rotating([lambda i=i: ok(L.ncp_copy(a[i].data_ptr(), dst[i].data_ptr(), nbytes, self._s())) for i in range(2)])
+        st = timer.rotating([lambda i=i: ok(L.ncp_copy(a[i].data_ptr(), dst[i].data_ptr(), nbytes, self._s())) for i in R])
         res["copy_kernel_GBps"] = round(2.0 * nbytes / (st["median"] * 1e-3) / 1e9, 1)
-        st = timer.rotating([lambda i=i: ok(L.ncp_read(a[i].data_ptr(), nbytes, sink.data_ptr(), self._s())) for i in range(2)])
+        st = timer.rotating([lambda i=i: ok(L.ncp_read(a[i].data_ptr(), nbytes, sink.data_ptr(), self._s())) for i in R])
         res["read_kernel_GBps"] = round(1.0 * nbytes / (st["median"] * 1e-3) / 1e9, 1)
-        st = timer.rotating([lambda i=i: ok(L.ncp_fill(dst[i].data_ptr(), nbytes, self._s())) for i in range(2)])
+        st = timer.rotating([lambda i=i: ok(L.ncp_fill(dst[i].data_ptr(), nbytes, self._s())) for i in R])
         res["fill_kernel_GBps"] = round(1.0 * nbytes / (st["median"] * 1e-3) / 1e9, 1)
         st = timer.rotating([lambda i=i: ok(L.ncp_mix94(a[i].data_ptr(), b[i].data_ptr(), c[i].data_ptr(), dst[i].data_ptr(),
-                                                       nbytes, self._s())) for i in range(2)])
+                                                       nbytes, self._s())) for i in R])
         res["mix_9to4_kernel_GBps"] = round(3.25 * nbytes / (st["median"] * 1e-3) / 1e9, 1)
-        st = timer.rotating([lambda: dst[0].copy_(a[0]), lambda: dst[1].copy_(a[1])])
-        res["torch_copy_GBps"] = round(2.0 * nbytes / (st["median"] * 1e-3) / 1e9, 1)
-        wgs, calls = 256 * 64, 512
-        st = timer.rotating([lambda: ok(L.ncp_philox(sink.data_ptr(), wgs, calls, self._s()))], reps=10, warm=2)
-        res["philox_Gcalls_per_s"] = round(wgs * 256 * calls / (st["median"] * 1e-3) / 1e9, 1)
+        if nbytes >= 1 << 29:
+            st = timer.rotating([lambda: dst[0].copy_(a[0]), lambda: dst[1].copy_(a[1])])
+            res["torch_copy_GBps"] = round(2.0 * nbytes / (st["median"] * 1e-3) / 1e9, 1)
+            wgs, calls = 256 * 64, 512
+            st = timer.rotating([lambda: ok(L.ncp_philox(sink.data_ptr(), wgs, calls, self._s()))], reps=10, warm=2)
+            res["philox_Gcalls_per_s"] = round(wgs * 256 * calls / (st["median"] * 1e-3) / 1e9, 1)
         res["probe_bytes"] = nbytes
         return res
 
@@ -372,7 +376,8 @@ def main():
     torch.cuda.set_device(0)
     timer = Timer(torch, np)
     if args.ceilings:
-        print(json.dumps({"ceilings": Probe(torch).ceilings(timer)}))
+        pr = Probe(torch)
+        print(json.dumps({"ceilings": pr.ceilings(timer), "ceilings_at_4d_bytes": pr.ceilings(timer, 4 * wl.D_RESNET50 // 16 * 16)}))
         return
 
     n = wl.NUM_WORKERS
@@ -461,7 +466,11 @@ def main():
                        "settle_steps": settle_steps, "wall_ms_per_step": ms_per_step,
                        "cold_aggregate_ms": cold_st["raw"], "rotated_encode_ms": enc_rot_st["raw"]}, f)
 
-    ceil = Probe(torch).ceilings(timer)
+    probe = Probe(torch)
+    ceil = probe.ceilings(timer)
+    # the same kernels on buffers the size of one config-2/3 vector (102 MB): what a launch of
+    # that size can reach, start and drain included
+    ceil_small = probe.ceilings(timer, 4 * d // 16 * 16)
 
     input_bytes = 4.0 * d * n
     value = input_bytes / (ms_per_step * 1e-3) / 1e9
@@ -536,6 +545,7 @@ def main():
             "frac_of_device_mix_kernel": round(agg_gbs / ceil["mix_9to4_kernel_GBps"], 4),
         },
         "device_ceilings": ceil,
+        "device_ceilings_at_4d_bytes": ceil_small,
     }
 
     if not args.no_secondary and not args.quick:
