@@ -280,7 +280,14 @@ def secondary_kernels(nc, wl, torch, np, timer):
     st = timer.rotating([lambda: nc.sparse_nat_aggregate(idx, exp5, sign5, k5, d5, out=out5)], reps=20, warm=3)
     res["config5_sparse_nat_aggregate_n8"] = _entry(
         st, 4.0 * d5 + n * k5 * (4 + 1.125 + 8), 4.0 * d5 * n,
-        "dense fp32 sum of 8 sparse messages: 4 B per coordinate written + per entry 5.125 B read and a 4 B read-modify-write", 1)
+        "dense fp32 sum of 8 sparse messages, one scatter launch per worker: 4 B per coordinate written + per entry "
+        "5.125 B read and a 4 B read-modify-write", 1)
+    ws5 = torch.empty(nc.sparse_aggregate_workspace_bytes(n, k5, d5), dtype=torch.uint8, device="cuda")
+    st = timer.rotating([lambda: nc.sparse_nat_aggregate_ws(idx, exp5, sign5, k5, d5, out=out5, workspace=ws5)], reps=20, warm=3)
+    res["config5_sparse_nat_aggregate_ws_n8"] = _entry(
+        st, 4.0 * d5 + n * k5 * 5.125, 4.0 * d5 * n,
+        "the same sum with the entries partitioned by output tile in a workspace: 4 B per coordinate written + "
+        "5.125 B per entry read (the partition's own traffic, about 50 B per entry, is not counted)", 1)
     return res
 
 
@@ -336,6 +343,8 @@ def pmc_probe(which, nc, wl, torch, np, step):
             idx, e5, s5 = nc.sparse_nat_encode_batch(x5, k5, float(np.float32(d5 / k5)), i)
             dst.copy_(src)
             nc.sparse_nat_aggregate(idx, e5, s5, k5, d5, out=out5)
+            dst.copy_(src)
+            nc.sparse_nat_aggregate_ws(idx, e5, s5, k5, d5, out=out5)
             dst.copy_(src)
         info.update({"d": d5, "k": k5, "n_workers": n})
     else:

@@ -326,6 +326,25 @@ nc_status nc_sparse_nat_aggregate(const uint32_t *idx, size_t idx_stride, const 
                                   const uint8_t *sign, size_t sign_stride, uint32_t n, uint64_t k, uint64_t d,
                                   float *out, void *stream);
 
+/* The same sum (Algorithm 1's master sum of sparse messages), bit for bit, for large d: the
+ * n*k entries are first sorted by output position inside a caller workspace (two counting
+ * sorts: at most 256 coarse bins, then tiles of 8192 positions), then every tile of out is
+ * built in on-chip memory, worker by worker in worker order, and written once, zeros included.
+ * The per-worker scatter of nc_sparse_nat_aggregate moves a whole cache line in and out of HBM
+ * for every 4-byte addition; this form moves about 50 bytes per entry and 4 bytes per output
+ * element.
+ *   workspace DEVICE, 16-byte aligned, at least nc_sparse_aggregate_workspace_bytes(n, k, d)
+ *   bytes (16*n*k for the sorted entries plus a few per cent for counters; 0 is returned for
+ *   arguments the call rejects); its contents need no initialisation and mean nothing
+ *   afterwards; calls that share a workspace must not overlap.
+ * Limits beyond those of nc_sparse_nat_aggregate: n <= 65535 and n*k < 2^32 (NC_ERR_INVALID);
+ * NC_ERR_WORKSPACE for a missing, misaligned or short workspace.  Indices >= d are ignored; a
+ * worker's indices must be distinct. */
+size_t nc_sparse_aggregate_workspace_bytes(uint32_t n, uint64_t k, uint64_t d);
+nc_status nc_sparse_nat_aggregate_ws(const uint32_t *idx, size_t idx_stride, const uint8_t *exp, size_t exp_stride,
+                                     const uint8_t *sign, size_t sign_stride, uint32_t n, uint64_t k, uint64_t d,
+                                     float *out, void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -289,6 +289,27 @@ nc_status nc_sparse_nat_aggregate(const uint32_t* idx, size_t idx_stride, const 
                                                 aligned(out, 16), (hipStream_t)stream));
 }
 
+static bool sparse_partition_ok(uint32_t n, uint64_t k, uint64_t d) {
+    return n >= 1 && n <= 65535 && d >= 1 && d <= (1ull << 32) && k >= 1 && k <= d && (uint64_t)n * k < (1ull << 32);
+}
+
+size_t nc_sparse_aggregate_workspace_bytes(uint32_t n, uint64_t k, uint64_t d) {
+    if (!sparse_partition_ok(n, k, d)) return 0;
+    return (size_t)sparse_partition_plan(n, k, d).bytes;
+}
+
+nc_status nc_sparse_nat_aggregate_ws(const uint32_t* idx, size_t idx_stride, const uint8_t* exp, size_t exp_stride,
+                                     const uint8_t* sign, size_t sign_stride, uint32_t n, uint64_t k, uint64_t d,
+                                     float* out, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!sparse_partition_ok(n, k, d)) return NC_ERR_INVALID;
+    if (!idx || !exp || !sign || !out) return NC_ERR_NULL;
+    if (n > 1 && (idx_stride < k || exp_stride < k || sign_stride < (k + 7) / 8)) return NC_ERR_INVALID;
+    if (!workspace || !aligned(workspace, 16) || workspace_bytes < sparse_partition_plan(n, k, d).bytes)
+        return NC_ERR_WORKSPACE;
+    return from_hip(launch_sparse_nat_aggregate_partitioned(idx, idx_stride, exp, exp_stride, sign, sign_stride, n, k, d,
+                                                            out, aligned(out, 16), workspace, (hipStream_t)stream));
+}
+
 nc_status nc_norm_compress(const float* norms, uint64_t count, uint64_t seed, uint32_t worker, uint8_t* exp_out,
                            float* norms_q_out, void* stream) {
     if (count >= (1ull << 31) * kBlock) return NC_ERR_INVALID;

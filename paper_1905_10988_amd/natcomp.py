@@ -84,6 +84,10 @@ def lib():
         L.nc_sparse_nat_encode_batch.argtypes = [_vp, _sz, _u32, _u64, _u64, ctypes.c_float, _u64, _u32, _vp, _sz,
                                                  _vp, _sz, _vp, _sz, _vp]
         L.nc_sparse_nat_aggregate.argtypes = [_vp, _sz, _vp, _sz, _vp, _sz, _u32, _u64, _u64, _vp, _vp]
+        L.nc_sparse_nat_aggregate_ws.argtypes = [_vp, _sz, _vp, _sz, _vp, _sz, _u32, _u64, _u64, _vp, _vp, _sz, _vp]
+        L.nc_sparse_nat_aggregate_ws.restype = ctypes.c_int
+        L.nc_sparse_aggregate_workspace_bytes.argtypes = [_u32, _u64, _u64]
+        L.nc_sparse_aggregate_workspace_bytes.restype = _sz
         L.nc_norm_compress.argtypes = [_vp, _u64, _u64, _u32, _vp, _vp, _vp]
         L.nc_norm_compress.restype = ctypes.c_int
         L.nc_master_nat.argtypes = [ctypes.POINTER(AggDesc), _u64, _u32, _u64, _vp, _vp, _vp]
@@ -372,6 +376,33 @@ def sparse_nat_aggregate(idx, exp, sign, k, d, out=None):
     assert out.numel() >= d
     _check(lib().nc_sparse_nat_aggregate(_ptr(idx), idx.shape[1], _ptr(exp), exp.shape[1], _ptr(sign), sign.shape[1],
                                          n, k, d, _ptr(out), _stream()))
+    return out
+
+
+def sparse_aggregate_workspace_bytes(n, k, d):
+    return int(lib().nc_sparse_aggregate_workspace_bytes(n, k, d))
+
+
+def sparse_nat_aggregate_ws(idx, exp, sign, k, d, out=None, workspace=None):
+    """nc_sparse_nat_aggregate_ws over the rows of 2-D tensors (row w = worker w); the workspace is a
+    uint8 tensor of at least sparse_aggregate_workspace_bytes(n, k, d) bytes (allocated here if None)."""
+    idx = _dev(idx, torch.int32, "idx")
+    exp = _dev(exp, torch.uint8, "exp")
+    sign = _dev(sign, torch.uint8, "sign")
+    assert idx.dim() == 2 and exp.dim() == 2 and sign.dim() == 2
+    n = idx.shape[0]
+    assert exp.shape[0] == n and sign.shape[0] == n
+    assert idx.shape[1] >= k and exp.shape[1] >= k and sign.shape[1] >= sign_bytes(k)
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=idx.device)
+    _dev(out, torch.float32, "out")
+    assert out.numel() >= d
+    if workspace is None:
+        workspace = torch.empty(max(1, sparse_aggregate_workspace_bytes(n, k, d)), dtype=torch.uint8, device=idx.device)
+    _dev(workspace, torch.uint8, "workspace")
+    _check(lib().nc_sparse_nat_aggregate_ws(_ptr(idx), idx.shape[1], _ptr(exp), exp.shape[1], _ptr(sign),
+                                            sign.shape[1], n, k, d, _ptr(out), _ptr(workspace), workspace.numel(),
+                                            _stream()))
     return out
 
 

@@ -115,6 +115,19 @@ def test_more_argument_errors_without_touching_the_gpu(nc):
     assert L.nc_sparse_nat_encode(one, 8, 9, ctypes.c_float(1.0), 0, 0, one, one, one, None) == 2
     assert L.nc_sparse_nat_aggregate(one, 0, one, 0, one, 0, 1, 4, 0, one, None) == 2
     assert L.nc_sparse_nat_aggregate(one, 0, one, 0, None, 0, 1, 4, 8, one, None) == 1
+    # the partitioned form: its own limits, then the workspace
+    L.nc_sparse_aggregate_workspace_bytes.restype = ctypes.c_size_t
+    L.nc_sparse_aggregate_workspace_bytes.argtypes = [ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint64]
+    need = L.nc_sparse_aggregate_workspace_bytes(8, 3_350_000, 335_000_000)
+    assert 16 * 8 * 3_350_000 <= need <= int(1.03 * 16 * 8 * 3_350_000)   # the four entry lists plus counters
+    assert L.nc_sparse_aggregate_workspace_bytes(0, 4, 8) == 0 and L.nc_sparse_aggregate_workspace_bytes(1, 9, 8) == 0
+    ws_args = [ctypes.c_void_p, ctypes.c_size_t] * 3 + [ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint64,
+                                                        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    L.nc_sparse_nat_aggregate_ws.argtypes = ws_args
+    assert L.nc_sparse_nat_aggregate_ws(one, 0, one, 0, one, 0, 70000, 4, 8, one, one, 1 << 20, None) == 2
+    assert L.nc_sparse_nat_aggregate_ws(one, 0, one, 0, one, 0, 1, 4, 8, None, one, 1 << 20, None) == 1
+    assert L.nc_sparse_nat_aggregate_ws(one, 0, one, 0, one, 0, 1, 4, 8, one, None, 0, None) == 4
+    assert L.nc_sparse_nat_aggregate_ws(one, 0, one, 0, one, 0, 1, 4, 8, one, one, 16, None) == 4
     # master compression wants C_nat planes
     desc = nc.AggDesc()
     desc.kind, desc.n, desc.d = nc.NC_KIND_DITHER, 1, 8

@@ -66,7 +66,7 @@ def test_config4_eight_workers_full_size(nc, oracle, wl):
 
 def test_config5_eight_workers_full_size(nc, oracle, wl):
     """Config 5: C_nat o S^k with d = 335,000,000, k = d/100, 8 workers encoded in one launch, then the
-    dense scatter-sum.  Every worker's whole message (indices, exponent bytes, sign bits) against the
+    dense scatter-sum in both its forms.  Every worker's whole message (indices, exponent bytes, sign bits) against the
     oracle's, and the whole dense sum against the oracle's worker-ordered binary32 sum."""
     d, n = wl.D_BERT_LARGE, wl.NUM_WORKERS
     k = d // 100
@@ -90,3 +90,8 @@ def test_config5_eight_workers_full_size(nc, oracle, wl):
     got = host(out)
     assert np.array_equal(got.view(np.uint32), o32.view(np.uint32))
     assert 0.95 * n * k < np.count_nonzero(got) <= n * k
+    # the partitioned form of the sum, the one bench.py times, on the same messages
+    del got, out
+    out = nc.sparse_nat_aggregate_ws(idx, exp, sign, k, d)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(out).view(np.uint32), o32.view(np.uint32))
