@@ -88,6 +88,9 @@ struct SparseScatterArgs {
 // The partitioned form of the scatter-sum: entries sorted by output position in a workspace,
 // then one workgroup per tile of 2^kSparseTileShift output positions.
 constexpr uint32_t kSparseTileShift = 13;
+struct SparsePiece {   // one chunk of the coarse-sorted lists: its bin and entries [begin, end)
+    uint32_t bin, begin, end, pad;
+};
 struct SparsePartitionArgs {
     const uint32_t* idx; size_t idx_stride; const uint8_t* exp; size_t exp_stride; const uint8_t* sign; size_t sign_stride;
     uint32_t n; uint64_t k, d; uint32_t coarse_shift, coarse_bins;
@@ -96,6 +99,8 @@ struct SparsePartitionArgs {
     uint32_t* tile_count; uint32_t* tile_base;  // per tile: entries, start in the tile-sorted lists
     uint32_t* hist1;         // [coarse bin][message chunk]: counts, then running offsets
     uint32_t* hist2;         // [chunk of the coarse-sorted lists][tile of its bin]: the same
+    SparsePiece* pieces;     // one per chunk of the coarse-sorted lists
+    uint32_t* total_chunks;  // how many of them there are
     uint32_t* idx1; uint32_t* meta1;   // the entries sorted by coarse bin
     uint32_t* idx2; uint32_t* meta2;   // the entries sorted by tile
     float* out;
@@ -103,7 +108,7 @@ struct SparsePartitionArgs {
 struct SparsePartitionPlan {
     uint32_t coarse_shift, coarse_bins, tile_bins;
     uint64_t tile_slots, tiles, entries, chunks1, chunks2;
-    uint64_t off_coarse_count, off_tile_count, off_tile_base, off_hist1, off_hist2, off_lists, list_bytes, bytes;
+    uint64_t off_coarse_count, off_tile_count, off_tile_base, off_hist1, off_hist2, off_pieces, off_lists, list_bytes, bytes;
 };
 SparsePartitionPlan sparse_partition_plan(uint32_t n, uint64_t k, uint64_t d);
 hipError_t launch_sparse_nat_aggregate_partitioned(const uint32_t* idx, size_t idx_stride, const uint8_t* exp,

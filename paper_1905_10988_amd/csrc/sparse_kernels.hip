@@ -213,21 +213,23 @@ __device__ __forceinline__ void chunk_histogram(const uint32_t (&i)[kPerLane], u
 
 // The chunk sorted by bin in LDS and written out as one run per bin: run_base(bin) is where this
 // chunk's run of the bin starts in the output lists.  hist, lstart, delta: nbins words each;
-// buf: kSparseChunk words.  Workgroups of kMoveLanes lanes; lanes own bins t*per_lane ..
-// t*per_lane + per_lane - 1 for the prefix sums (per_lane = nbins / kMoveLanes, at least 1).
+// buf: kSparseChunk entries (index in the low word, meta in the high word).  Workgroups of
+// kMoveLanes lanes; lanes own bins t*per_lane .. t*per_lane + per_lane - 1 for the prefix sums
+// (per_lane = nbins / kMoveLanes, at least 1).  (Entries written straight from the lanes that
+// hold them, 4 bytes here and 4 bytes there, take twice as long as the runs out of LDS.)
 template <class BinOf, class RunBase>
 __device__ __forceinline__ void chunk_sort_and_write(const uint32_t (&i)[kMovePerLane], const uint32_t (&meta)[kMovePerLane],
                                                      uint32_t have, uint32_t nbins, uint32_t* hist, uint32_t* lstart,
-                                                     uint32_t* delta, uint32_t* buf, uint32_t* scan_lds, BinOf bin_of,
+                                                     uint32_t* delta, uint64_t* buf, uint32_t* scan_lds, BinOf bin_of,
                                                      RunBase run_base, uint32_t* __restrict__ out_idx,
                                                      uint32_t* __restrict__ out_meta) {
     for (uint32_t b = threadIdx.x; b < nbins; b += kMoveLanes) hist[b] = 0u;
     __syncthreads();
-    uint32_t at[kMovePerLane];  // rank inside the bin, then position in the sorted chunk
+    uint32_t rank[kMovePerLane];
 #pragma unroll
     for (uint32_t r = 0; r < kMovePerLane; ++r) {
-        at[r] = 0u;
-        if ((have >> r) & 1u) at[r] = atomicAdd(&hist[bin_of(i[r])], 1u);
+        rank[r] = 0u;
+        if ((have >> r) & 1u) rank[r] = atomicAdd(&hist[bin_of(i[r])], 1u);
     }
     const uint32_t per_lane = nbins > (uint32_t)kMoveLanes ? nbins / kMoveLanes : 1u;
     const uint32_t b0 = threadIdx.x * per_lane;
@@ -247,33 +249,19 @@ __device__ __forceinline__ void chunk_sort_and_write(const uint32_t (&i)[kMovePe
     }
     __syncthreads();
 #pragma unroll
-    for (uint32_t r = 0; r < kMovePerLane; ++r) {
-        if ((have >> r) & 1u) {
-            at[r] += lstart[bin_of(i[r])];
-            buf[at[r]] = i[r];
-        }
-    }
-    __syncthreads();
-    uint32_t dest[kMovePerLane];
-#pragma unroll
-    for (uint32_t r = 0; r < kMovePerLane; ++r) {
-        const uint32_t q = threadIdx.x + kMoveLanes * r;
-        dest[r] = 0u;
-        if (q < total) {
-            const uint32_t v = buf[q];
-            dest[r] = delta[bin_of(v)] + q;
-            out_idx[dest[r]] = v;
-        }
-    }
-    __syncthreads();
-#pragma unroll
     for (uint32_t r = 0; r < kMovePerLane; ++r)
-        if ((have >> r) & 1u) buf[at[r]] = meta[r];
+        if ((have >> r) & 1u) buf[lstart[bin_of(i[r])] + rank[r]] = ((uint64_t)meta[r] << 32) | i[r];
     __syncthreads();
 #pragma unroll
     for (uint32_t r = 0; r < kMovePerLane; ++r) {
         const uint32_t q = threadIdx.x + kMoveLanes * r;
-        if (q < total) out_meta[dest[r]] = buf[q];
+        if (q < total) {
+            const uint64_t e = buf[q];
+            const uint32_t v = (uint32_t)e;
+            const uint32_t dst = delta[bin_of(v)] + q;
+            out_idx[dst] = v;
+            out_meta[dst] = (uint32_t)(e >> 32);
+        }
     }
 }
 
@@ -324,7 +312,7 @@ __global__ __launch_bounds__(kBlock) void sparse_scan_coarse_kernel(SparsePartit
 // totals (every workgroup computes them itself: at most 256 words).
 __global__ __launch_bounds__(kMoveLanes) void sparse_move_coarse_kernel(SparsePartitionArgs a) {
     __shared__ uint32_t hist[kBlock], lstart[kBlock], delta[kBlock], base[kBlock];
-    __shared__ uint32_t buf[kSparseChunk];
+    __shared__ uint64_t buf[kSparseChunk];
     __shared__ uint32_t scan_lds[kMoveLanes / 64];
     const uint32_t w = blockIdx.y;
     const uint32_t* __restrict__ idx = a.idx + (size_t)w * a.idx_stride;
@@ -451,25 +439,43 @@ __global__ __launch_bounds__(kBlock) void sparse_scan_tiles_kernel(SparsePartiti
             at += counts[q];
         }
     }
+    // what pass 6 needs to know about each of this bin's chunks, so that it starts with one load
+    for (uint32_t c = threadIdx.x; c < pc.begin; c += kBlock) {
+        const uint32_t b = pc.bin_base + c * kSparseChunk, e = pc.bin_base + pc.end;
+        a.pieces[pc.first_chunk + c] = SparsePiece{blockIdx.x, b, e - b > kSparseChunk ? b + kSparseChunk : e, 0u};
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) *a.total_chunks = total_chunks;
 }
 
-// Pass 6: entries moved into their tiles.
+// Pass 6: entries moved into their tiles.  MAX_BINS: 256 (two workgroups fit a CU's LDS) or
+// kMaxTileBins (d beyond 2^29).
+template <uint32_t MAX_BINS>
 __global__ __launch_bounds__(kMoveLanes) void sparse_move_tiles_kernel(SparsePartitionArgs a) {
-    __shared__ uint32_t hist[kMaxTileBins], lstart[kMaxTileBins], delta[kMaxTileBins];
-    __shared__ uint32_t buf[kSparseChunk];
+    __shared__ uint32_t hist[MAX_BINS], lstart[MAX_BINS], delta[MAX_BINS];
+    __shared__ uint64_t buf[kSparseChunk];
     __shared__ uint32_t scan_lds[kMoveLanes / 64];
-    __shared__ CoarsePiece slot;
-    CoarsePiece pc;
-    if (!coarse_piece<kMoveLanes>(a, blockIdx.x, scan_lds, &slot, pc)) return;
+    if (blockIdx.x >= *a.total_chunks) return;  // (the grid is sized for the worst case)
+    const SparsePiece pc = a.pieces[blockIdx.x];
     const uint32_t tile_bins = 1u << (a.coarse_shift - kSparseTileShift);
+    // where this chunk's run of each tile starts, for the tiles whose prefix sums the lane owns
+    constexpr uint32_t kOwn = kMaxTileBins / kMoveLanes;
+    const uint32_t per_lane = tile_bins > (uint32_t)kMoveLanes ? tile_bins / kMoveLanes : 1u;
+    const uint32_t t0 = threadIdx.x * per_lane;
+    const uint32_t* __restrict__ offsets = a.hist2 + (size_t)blockIdx.x * tile_bins;
+    const uint32_t* __restrict__ bases = a.tile_base + (size_t)pc.bin * tile_bins;
+    uint32_t run[kOwn];
+#pragma unroll
+    for (uint32_t q = 0; q < kOwn; ++q) {
+        const uint32_t t = t0 + q < tile_bins ? t0 + q : 0u;  // (lanes without a tile: any valid one)
+        run[q] = bases[t] + offsets[t];
+    }
     uint32_t i[kMovePerLane], meta[kMovePerLane];
     const uint32_t have = load_chunk_words<kMoveLanes>(a.idx1, pc.begin, pc.end, i);
     load_chunk_words<kMoveLanes>(a.meta1, pc.begin, pc.end, meta);
-    const uint32_t* __restrict__ offsets = a.hist2 + (size_t)blockIdx.x * tile_bins;
-    const uint32_t* __restrict__ bases = a.tile_base + (size_t)pc.bin * tile_bins;
+    static_assert(kOwn == 2, "run_base below picks one of two");
     chunk_sort_and_write(i, meta, have, tile_bins, hist, lstart, delta, buf, scan_lds,
                          [tile_bins](uint32_t v) { return (v >> kSparseTileShift) & (tile_bins - 1u); },
-                         [&](uint32_t t) { return bases[t] + offsets[t]; }, a.idx2, a.meta2);
+                         [&](uint32_t t) { return t == t0 ? run[0] : run[1]; }, a.idx2, a.meta2);
 }
 
 // Pass 7: one workgroup per tile of the dense vector.  The tile starts as +0.0 (the scatter
@@ -562,11 +568,12 @@ SparsePartitionPlan sparse_partition_plan(uint32_t n, uint64_t k, uint64_t d) {
     p.chunks2 = p.entries / kSparseChunk + p.coarse_bins;  // upper bound: one ragged chunk per bin
     auto up = [](uint64_t b) { return (b + 255) & ~255ull; };
     p.off_coarse_count = 0;
-    p.off_tile_count = up(4 * 256);
+    p.off_tile_count = up(4 * 257);   // (the word after the 256 counts: chunks of the coarse-sorted lists)
     p.off_tile_base = p.off_tile_count + up(4 * p.tile_slots);
     p.off_hist1 = p.off_tile_base + up(4 * p.tile_slots);
     p.off_hist2 = p.off_hist1 + up(4 * p.coarse_bins * p.chunks1);
-    p.off_lists = p.off_hist2 + up(4 * p.chunks2 * p.tile_bins);
+    p.off_pieces = p.off_hist2 + up(4 * p.chunks2 * p.tile_bins);
+    p.off_lists = p.off_pieces + up(16 * p.chunks2);
     p.list_bytes = up(4 * p.entries);
     p.bytes = p.off_lists + 4 * p.list_bytes;
     return p;
@@ -587,6 +594,8 @@ hipError_t launch_sparse_nat_aggregate_partitioned(const uint32_t* idx, size_t i
     a.tile_base = words(p.off_tile_base);
     a.hist1 = words(p.off_hist1);
     a.hist2 = words(p.off_hist2);
+    a.pieces = reinterpret_cast<SparsePiece*>(ws + p.off_pieces);
+    a.total_chunks = words(p.off_coarse_count) + 256;
     a.idx1 = words(p.off_lists);
     a.meta1 = words(p.off_lists + p.list_bytes);
     a.idx2 = words(p.off_lists + 2 * p.list_bytes);
@@ -604,7 +613,8 @@ hipError_t launch_sparse_nat_aggregate_partitioned(const uint32_t* idx, size_t i
     if ((e = hipGetLastError()) != hipSuccess) return e;
     sparse_scan_tiles_kernel<<<p.coarse_bins, kBlock, 0, stream>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    sparse_move_tiles_kernel<<<(unsigned)p.chunks2, kMoveLanes, 0, stream>>>(a);
+    if (p.tile_bins <= 256) sparse_move_tiles_kernel<256><<<(unsigned)p.chunks2, kMoveLanes, 0, stream>>>(a);
+    else sparse_move_tiles_kernel<kMaxTileBins><<<(unsigned)p.chunks2, kMoveLanes, 0, stream>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (out_aligned) sparse_tile_sum_kernel<true><<<(unsigned)p.tiles, kBlock, 0, stream>>>(a);
     else sparse_tile_sum_kernel<false><<<(unsigned)p.tiles, kBlock, 0, stream>>>(a);
