@@ -1182,15 +1182,16 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
 }
 
 // Plain decoder (n = 1) for the nibble formats, vector path: the lean special case of the
-// aggregate kernel.  The lane's 8 codes are loaded first; the first wavefront tabulates the 16
-// values a nibble can stand for in this chunk's segment; chunks that straddle segments (and the
-// ragged end) decode arithmetically.  Results leave through the LDS transpose.
+// aggregate kernel.  The lane's 8 codes are loaded first; the 16 values a nibble can stand for
+// in this chunk's segment are kept one per lane and looked up with lane permutes; chunks that
+// straddle segments (and the ragged end) decode arithmetically.  Results leave through the LDS
+// transpose.
 // WHOLE: the chunk has kChunk elements.  Whole chunks and the ragged last one run separate copies
 // of the body, so that a whole chunk has no branch between the probe, the code loads and the
 // probe's use, and no join of the two copies' code words afterwards.
 template <int FMT, bool WG_SEARCH, bool WHOLE>
 __device__ __forceinline__ void dither_decode_chunk(const DitherAggregateArgs& a, uint64_t cb, uint64_t ce,
-                                                    float* table, u32x4* tile, SegSlot& slot, uint32_t* bnd) {
+                                                    u32x4* tile, SegSlot& slot, uint32_t* bnd) {
     const Segs& sg = a.segs;
     const uint32_t grp_local = threadIdx.x;
     const uint32_t l0 = grp_local * 8;
@@ -1217,17 +1218,16 @@ __device__ __forceinline__ void dither_decode_chunk(const DitherAggregateArgs& a
     const bool one_segment = hit.end >= ce;
     uint32_t bits[8];
     if (one_segment) {
-        if (threadIdx.x < 16) {
-            const float norm = a.norm8 ? load_norm(a, s0) : hit.aux;
-            table[threadIdx.x] = (FMT == kFmtFused)
-                                     ? dither_value(norm, a.s, threadIdx.x & 7u, threadIdx.x >> 3, a.standard)
-                                     : dither_value(norm, a.s, threadIdx.x, 0u, a.standard);
-        }
-        __syncthreads();
-        asm volatile("" : "+v"(cw), "+v"(sb));  // no table addresses computed ahead of the barrier
+        // The 16 values a nibble can stand for live one per lane (lane l holds the value of nibble
+        // l mod 16) and are looked up with a lane permute: no table in memory and no barrier.
+        const uint32_t nib_of_lane = threadIdx.x & 15u;
+        const float norm = a.norm8 ? load_norm(a, s0) : hit.aux;
+        const uint32_t value_of_lane =
+            f32_bits((FMT == kFmtFused) ? dither_value(norm, a.s, nib_of_lane & 7u, nib_of_lane >> 3, a.standard)
+                                        : dither_value(norm, a.s, nib_of_lane, 0u, a.standard));
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            uint32_t v = f32_bits(table[(cw >> (4 * j)) & 15u]);
+            uint32_t v = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(((cw >> (4 * j)) & 15u) << 2), (int)value_of_lane);
             if (FMT == kFmtNibble) v |= (sb << (31 - j)) & 0x80000000u;
             bits[j] = v;
         }
@@ -1280,13 +1280,12 @@ __device__ __forceinline__ void dither_decode_chunk(const DitherAggregateArgs& a
 
 template <int FMT, bool WG_SEARCH>
 __global__ __launch_bounds__(kBlock) void dither_decode_kernel(DitherAggregateArgs a) {
-    __shared__ float table[16];
     __shared__ u32x4 tile[2 * kBlock];
     __shared__ SegSlot slot;
     __shared__ uint32_t bnd[kBlock];
     const uint64_t cb = (uint64_t)blockIdx.x * kChunk;
-    if (cb + kChunk <= a.segs.d) dither_decode_chunk<FMT, WG_SEARCH, true>(a, cb, cb + kChunk, table, tile, slot, bnd);
-    else dither_decode_chunk<FMT, WG_SEARCH, false>(a, cb, a.segs.d, table, tile, slot, bnd);
+    if (cb + kChunk <= a.segs.d) dither_decode_chunk<FMT, WG_SEARCH, true>(a, cb, cb + kChunk, tile, slot, bnd);
+    else dither_decode_chunk<FMT, WG_SEARCH, false>(a, cb, a.segs.d, tile, slot, bnd);
 }
 
 // ------------------------------------------------------------------------ compressed norm
