@@ -146,6 +146,9 @@ class Probe:
         st = timer.rotating([lambda i=i: ok(L.ncp_mix94(a[i].data_ptr(), b[i].data_ptr(), c[i].data_ptr(), dst[i].data_ptr(),
                                                        nbytes, self._s())) for i in R])
         res["mix_9to4_kernel_GBps"] = round(3.25 * nbytes / (st["median"] * 1e-3) / 1e9, 1)
+        if nbytes < 1 << 28:  # fits the last-level cache: what reading the same buffer again is worth
+            st = timer.rotating([lambda: ok(L.ncp_read(a[0].data_ptr(), nbytes, sink.data_ptr(), self._s()))])
+            res["read_kernel_same_buffer_GBps"] = round(1.0 * nbytes / (st["median"] * 1e-3) / 1e9, 1)
         if nbytes >= 1 << 29:
             st = timer.rotating([lambda: dst[0].copy_(a[0]), lambda: dst[1].copy_(a[1])])
             res["torch_copy_GBps"] = round(2.0 * nbytes / (st["median"] * 1e-3) / 1e9, 1)
