@@ -32,53 +32,44 @@ __device__ __forceinline__ uint32_t seg_find(const Segs& sg, uint64_t i) {
     }
     return sg.bucket ? (uint32_t)(i / sg.bucket) : 0u;
 }
-// The segment of a workgroup-uniform position together with what the kernels need next: its
-// bounds and, if aux is given, aux[segment] (a norm or its reciprocal).  With at most kBlock
-// segments the whole workgroup searches at once: lane t loads segment t's bounds and aux value
-// in one round of loads and the lane whose segment holds i publishes them, which replaces the
-// dependent chain binary search -> bounds -> aux.
-// The search comes in two halves so that a kernel can put its own streaming loads between
-// them: seg_probe_issue only issues the lane's loads; seg_probe_finish compares, publishes
-// through `slot` (LDS) and holds the workgroup's one barrier.  Loads return in issue order, so
-// a probe issued ahead of the kernel's data loads is back while those are still in flight, and
-// the search costs no round trip of its own (measured on a 25.6 M-element norm pass: 19.6 us
-// with the search after the data loads, 16.6 us with the probe issued first, 16.8 us with no
-// search at all).  All lanes must call both halves, once per kernel (`slot` is not reused).
+// The segment of a wavefront-uniform position together with what the kernels need next: its
+// bounds and, if aux is given, aux[segment] (a norm or its reciprocal).  With segment offsets
+// the binary search runs on the scalar unit: every step is a scalar load through the scalar data
+// cache (the offsets and aux arrays are only read by the kernels that search them), counted by
+// lgkmcnt, so the search neither waits for the kernel's vector loads in flight nor needs LDS or a
+// barrier.  (A search by the whole workgroup, lane t testing segment t and publishing through
+// LDS, costs the same in the norm pass and 1.3 us of 25.9 more in the config-3 decoder; the same
+// binary search with vector loads waits for the data loads at every step: 22.3 us for a norm
+// pass of 19.0.)  i must be wavefront-uniform.
 struct SegHit {
     uint32_t s;
     float aux;
     uint64_t begin, end;
 };
-struct SegProbe {
-    uint64_t begin, end;
-    float aux;
-    uint32_t s;
-};
-struct SegSlot {  // LDS: the published record and, per wavefront, whether one of its lanes published
-    SegHit hit;
-    uint32_t found[kBlock / 64];
-};
-// (The host decides: offsets given, at most kBlock segments, workgroups of kBlock lanes.  The
-// kernels take the decision as a template parameter, because a run-time branch around the
-// probe's loads makes the compiler wait for them before the kernel's own loads are issued.)
-inline bool seg_probe_by_workgroup(const Segs& sg) {
-    return sg.offsets && sg.num_segments > 0 && sg.num_segments <= (uint32_t)kBlock;
+__device__ __forceinline__ uint64_t scalar_load_u64(const uint64_t* base, uint32_t k) {
+    uint64_t v;
+    asm volatile("s_load_dwordx2 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(base), "s"(k * 8u));
+    return v;
 }
-template <bool BY_WORKGROUP>
-__device__ __forceinline__ SegProbe seg_probe_issue(const Segs& sg, const float* __restrict__ aux) {
-    SegProbe p{0ull, 0ull, 0.0f, 0u};
-    if (BY_WORKGROUP) {
-        // lanes past the last segment probe the last one again and publish the same record
-        p.s = threadIdx.x < sg.num_segments ? threadIdx.x : sg.num_segments - 1;
-        p.begin = sg.offsets[p.s];
-        p.end = sg.offsets[p.s + 1];
-        p.aux = aux ? aux[p.s] : 0.0f;
-    }
-    return p;
+__device__ __forceinline__ float scalar_load_f32(const float* base, uint32_t k) {
+    float v;
+    asm volatile("s_load_dword %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(base), "s"(k * 4u));
+    return v;
 }
-// The same answer from a binary search by every lane (any number of segments; no LDS, no barrier).
 __device__ __forceinline__ SegHit seg_find_hit(const Segs& sg, uint64_t i, const float* __restrict__ aux) {
     SegHit h;
+    if (sg.offsets && sg.num_segments < (1u << 29)) {  // (byte offsets of the scalar loads fit 32 bits)
+        uint32_t lo = 0, hi = sg.num_segments;  // offsets[lo] <= i < offsets[hi]
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (scalar_load_u64(sg.offsets, mid) <= i) lo = mid; else hi = mid;
+        }
+        h.s = lo;
+        h.begin = scalar_load_u64(sg.offsets, lo);
+        h.end = scalar_load_u64(sg.offsets, lo + 1);
+        h.aux = aux ? scalar_load_f32(aux, lo) : 0.0f;
+        return h;
+    }
     h.s = seg_find(sg, i);
     if (sg.offsets) {
         h.begin = sg.offsets[h.s];
@@ -89,21 +80,6 @@ __device__ __forceinline__ SegHit seg_find_hit(const Segs& sg, uint64_t i, const
     }
     h.aux = aux ? aux[h.s] : 0.0f;
     return h;
-}
-template <bool BY_WORKGROUP>
-__device__ __forceinline__ SegHit seg_probe_finish(const Segs& sg, uint64_t i, const SegProbe& p,
-                                                   const float* __restrict__ aux, SegSlot* slot) {
-    if (!BY_WORKGROUP) return seg_find_hit(sg, i, aux);
-    const bool holds = p.begin <= i && i < p.end;  // at most one non-empty segment holds i
-    if (holds) slot->hit = SegHit{p.s, p.aux, p.begin, p.end};
-    const bool wave_holds = __ballot(holds) != 0;
-    if ((threadIdx.x & 63) == 0) slot->found[threadIdx.x >> 6] = wave_holds;
-    __syncthreads();
-    bool any = false;
-#pragma unroll
-    for (int w = 0; w < kBlock / 64; ++w) any |= slot->found[w] != 0;
-    if (!any) return SegHit{0u, 0.0f, 0ull, 0ull};  // offsets that do not cover i
-    return slot->hit;
 }
 __device__ __forceinline__ uint64_t seg_begin(const Segs& sg, uint32_t s) {
     if (sg.offsets) return sg.offsets[s];
@@ -736,10 +712,9 @@ __device__ __forceinline__ void partial_by_segments(const DitherEncodeArgs& a, u
     }
 }
 
-template <bool FAST, bool WG_SEARCH>
+template <bool FAST>
 __global__ __launch_bounds__(kBlock) void dither_partial_kernel(DitherEncodeArgs a) {
     __shared__ NormAcc scratch[kBlock / 64];
-    __shared__ SegSlot slot;
     __shared__ uint32_t bnd[kBlock];
     __shared__ double piece_part[kBlock * (kBlock / 64)];  // [piece][wavefront]
     constexpr int kQuads = kNormChunk / 4 / kBlock;  // quads per lane
@@ -750,14 +725,12 @@ __global__ __launch_bounds__(kBlock) void dither_partial_kernel(DitherEncodeArgs
         partial_by_segments(a, cb, ce, seg_find(sg, cb), scratch);
         return;
     }
-    // A whole chunk: the probe first, then unconditional vector loads, and no branch between the
-    // probe and its use, so that the wait for the probe leaves the chunk's loads in flight.
-    const SegProbe probe = seg_probe_issue<WG_SEARCH>(sg, nullptr);
+    // A whole chunk: unconditional vector loads, all issued before the segment search.
     u32x4 v[kQuads];
     const u32x4* __restrict__ xv = reinterpret_cast<const u32x4*>(a.x + cb) + threadIdx.x;
 #pragma unroll
     for (int k = 0; k < kQuads; ++k) v[k] = load_stream(xv + k * kBlock);
-    const SegHit hit = seg_probe_finish<WG_SEARCH>(sg, cb, probe, nullptr, &slot);
+    const SegHit hit = seg_find_hit(sg, cb, nullptr);
     const uint32_t s0 = hit.s;
     // keep the loaded values opaque up to here, so that nothing is computed from them (and held
     // in registers) ahead of the search
@@ -1047,11 +1020,10 @@ __device__ __forceinline__ float dither_sum_one(const DitherAggregateArgs& a, ui
 // (worker, bucket of the chunk); a lane's 8 elements share a bucket.  Everything else (byte
 // codes, chunks that straddle other segment boundaries) is decoded arithmetically:
 // norm * 2^(c-s).
-template <int FMT, bool VEC, int TABLE, bool WG_SEARCH>
+template <int FMT, bool VEC, int TABLE>
 __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregateArgs a) {
     __shared__ float table[TABLE];
     __shared__ u32x4 tile[2 * kBlock];
-    __shared__ SegSlot slot;
     __shared__ uint32_t bnd[kBlock];
     const Segs& sg = a.segs;
     const uint64_t cb = (uint64_t)blockIdx.x * kChunk;
@@ -1065,16 +1037,12 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
     constexpr bool kMulti = TABLE > 256;
     const uint32_t n_first = a.n >= 8 ? 8u : (a.n == 1 ? 1u : 0u);  // 2..7 workers: no preload
     uint32_t cw0[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u}, sb0[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-    // The segment search is issued ahead of the preload and finished after it.  (The preload is
-    // conditional, so the compiler lets the search wait for it; giving whole chunks a branch-free
-    // copy of this part was tried and moves the wait to the point where the copies join.)
-    const SegProbe probe = seg_probe_issue<WG_SEARCH && !kMulti>(sg, nullptr);
     if (kTables && count == 8) {
         if (n_first == 8) dither_load_codes<FMT, 8>(a, grp, 0, cw0, sb0);
         else if (n_first == 1) dither_load_codes<FMT, 1>(a, grp, 0, cw0, sb0);
     }
     SegHit hit{0u, 0.0f, 0ull, 0ull};
-    if (!kMulti) hit = seg_probe_finish<WG_SEARCH>(sg, cb, probe, nullptr, &slot);
+    if (!kMulti) hit = seg_find_hit(sg, cb, nullptr);  // (scalar loads: the preload stays in flight)
     uint32_t s0, log2_nbk = 0, lane_bucket = 0, nseg = 0;
     uint64_t s0_begin = 0;
     bool one_segment;
@@ -1186,34 +1154,25 @@ __global__ __launch_bounds__(kBlock) void dither_aggregate_kernel(DitherAggregat
 // in this chunk's segment are kept one per lane and looked up with lane permutes; chunks that
 // straddle segments (and the ragged end) decode arithmetically.  Results leave through the LDS
 // transpose.
-// WHOLE: the chunk has kChunk elements.  Whole chunks and the ragged last one run separate copies
-// of the body, so that a whole chunk has no branch between the probe, the code loads and the
-// probe's use, and no join of the two copies' code words afterwards.
-template <int FMT, bool WG_SEARCH, bool WHOLE>
-__device__ __forceinline__ void dither_decode_chunk(const DitherAggregateArgs& a, uint64_t cb, uint64_t ce,
-                                                    u32x4* tile, SegSlot& slot, uint32_t* bnd) {
+template <int FMT>
+__global__ __launch_bounds__(kBlock) void dither_decode_kernel(DitherAggregateArgs a) {
+    __shared__ u32x4 tile[2 * kBlock];
+    __shared__ uint32_t bnd[kBlock];
     const Segs& sg = a.segs;
+    const uint64_t cb = (uint64_t)blockIdx.x * kChunk;
+    const uint64_t ce = cb + kChunk < sg.d ? cb + kChunk : sg.d;
     const uint32_t grp_local = threadIdx.x;
     const uint32_t l0 = grp_local * 8;
     const uint32_t len = (uint32_t)(ce - cb);
     const uint32_t count = l0 >= len ? 0u : (len - l0 < 8 ? len - l0 : 8u);
     const uint32_t* __restrict__ code_base = reinterpret_cast<const uint32_t*>(a.code + (cb >> 1));
     const uint8_t* __restrict__ sign_base = a.sign + (cb >> 3);
-    const float* __restrict__ aux = a.norm8 ? nullptr : a.norms;
     uint32_t cw = 0, sb = 0;
-    SegHit hit;
-    if (WHOLE) {
-        const SegProbe probe = seg_probe_issue<WG_SEARCH>(sg, aux);
+    if (count == 8) {
         cw = load_stream(code_base + grp_local);
         if (FMT == kFmtNibble) sb = load_stream(sign_base + grp_local);
-        hit = seg_probe_finish<WG_SEARCH>(sg, cb, probe, aux, &slot);
-    } else {
-        if (count == 8) {
-            cw = load_stream(code_base + grp_local);
-            if (FMT == kFmtNibble) sb = load_stream(sign_base + grp_local);
-        }
-        hit = seg_find_hit(sg, cb, aux);
     }
+    const SegHit hit = seg_find_hit(sg, cb, a.norm8 ? nullptr : a.norms);  // (scalar loads: the code loads stay in flight)
     const uint32_t s0 = hit.s;
     const bool one_segment = hit.end >= ce;
     uint32_t bits[8];
@@ -1276,16 +1235,6 @@ __device__ __forceinline__ void dither_decode_chunk(const DitherAggregateArgs& a
             a.out[i] = dither_sum_one<FMT>(a, i, s);
         }
     }
-}
-
-template <int FMT, bool WG_SEARCH>
-__global__ __launch_bounds__(kBlock) void dither_decode_kernel(DitherAggregateArgs a) {
-    __shared__ u32x4 tile[2 * kBlock];
-    __shared__ SegSlot slot;
-    __shared__ uint32_t bnd[kBlock];
-    const uint64_t cb = (uint64_t)blockIdx.x * kChunk;
-    if (cb + kChunk <= a.segs.d) dither_decode_chunk<FMT, WG_SEARCH, true>(a, cb, cb + kChunk, tile, slot, bnd);
-    else dither_decode_chunk<FMT, WG_SEARCH, false>(a, cb, a.segs.d, tile, slot, bnd);
 }
 
 // ------------------------------------------------------------------------ compressed norm
@@ -1385,8 +1334,7 @@ static hipError_t launch_segment(const DitherEncodeArgs& a, hipStream_t st) {
     const unsigned norm_chunks = (unsigned)((a.segs.d + kNormChunk - 1) / kNormChunk);
     const unsigned nseg = (unsigned)(a.segs.offsets ? a.segs.num_segments
                                      : a.segs.bucket ? (a.segs.d + a.segs.bucket - 1) / a.segs.bucket : 1);
-    if (seg_probe_by_workgroup(a.segs)) dither_partial_kernel<FAST, true><<<norm_chunks, kBlock, 0, st>>>(a);
-    else dither_partial_kernel<FAST, false><<<norm_chunks, kBlock, 0, st>>>(a);
+    dither_partial_kernel<FAST><<<norm_chunks, kBlock, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     dither_finalize_kernel<<<nseg, kBlock, 0, st>>>(a);
@@ -1404,12 +1352,12 @@ hipError_t launch_dither_segment_encode(const DitherEncodeArgs& a, bool fast, hi
     return fast ? launch_segment<true>(a, stream) : launch_segment<false>(a, stream);
 }
 
-template <bool FAST, bool WG_SEARCH>
+template <bool FAST>
 static hipError_t launch_agg(const DitherAggregateArgs& a, hipStream_t st) {
     const unsigned chunks = (unsigned)((a.segs.d + kChunk - 1) / kChunk);
     if (FAST && a.n == 1 && a.fmt != kFmtByte) {  // plain decoder
-        if (a.fmt == kFmtFused) dither_decode_kernel<kFmtFused, WG_SEARCH><<<chunks, kBlock, 0, st>>>(a);
-        else dither_decode_kernel<kFmtNibble, WG_SEARCH><<<chunks, kBlock, 0, st>>>(a);
+        if (a.fmt == kFmtFused) dither_decode_kernel<kFmtFused><<<chunks, kBlock, 0, st>>>(a);
+        else dither_decode_kernel<kFmtNibble><<<chunks, kBlock, 0, st>>>(a);
         return hipGetLastError();
     }
     const uint32_t bucket = a.segs.bucket;
@@ -1417,21 +1365,20 @@ static hipError_t launch_agg(const DitherAggregateArgs& a, hipStream_t st) {
         DitherAggregateArgs b = a;  // several whole buckets per chunk: tables per (worker, bucket)
         b.log2_bucket = 6;
         while ((1u << b.log2_bucket) < bucket) ++b.log2_bucket;
-        if (a.fmt == kFmtFused) dither_aggregate_kernel<kFmtFused, FAST, 4096, false><<<chunks, kBlock, 0, st>>>(b);
-        else dither_aggregate_kernel<kFmtNibble, FAST, 4096, false><<<chunks, kBlock, 0, st>>>(b);
+        if (a.fmt == kFmtFused) dither_aggregate_kernel<kFmtFused, FAST, 4096><<<chunks, kBlock, 0, st>>>(b);
+        else dither_aggregate_kernel<kFmtNibble, FAST, 4096><<<chunks, kBlock, 0, st>>>(b);
         return hipGetLastError();
     }
     switch (a.fmt) {
-        case kFmtFused: dither_aggregate_kernel<kFmtFused, FAST, 256, WG_SEARCH><<<chunks, kBlock, 0, st>>>(a); break;
-        case kFmtNibble: dither_aggregate_kernel<kFmtNibble, FAST, 256, WG_SEARCH><<<chunks, kBlock, 0, st>>>(a); break;
-        default: dither_aggregate_kernel<kFmtByte, FAST, 256, WG_SEARCH><<<chunks, kBlock, 0, st>>>(a); break;
+        case kFmtFused: dither_aggregate_kernel<kFmtFused, FAST, 256><<<chunks, kBlock, 0, st>>>(a); break;
+        case kFmtNibble: dither_aggregate_kernel<kFmtNibble, FAST, 256><<<chunks, kBlock, 0, st>>>(a); break;
+        default: dither_aggregate_kernel<kFmtByte, FAST, 256><<<chunks, kBlock, 0, st>>>(a); break;
     }
     return hipGetLastError();
 }
 
 hipError_t launch_dither_aggregate(const DitherAggregateArgs& a, bool fast, hipStream_t stream) {
-    if (seg_probe_by_workgroup(a.segs)) return fast ? launch_agg<true, true>(a, stream) : launch_agg<false, true>(a, stream);
-    return fast ? launch_agg<true, false>(a, stream) : launch_agg<false, false>(a, stream);
+    return fast ? launch_agg<true>(a, stream) : launch_agg<false>(a, stream);
 }
 
 }  // namespace natcomp
