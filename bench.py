@@ -172,6 +172,16 @@ def secondary_kernels(nc, wl, torch, np, timer):
     nseg = off.size - 1
     n = wl.NUM_WORKERS
 
+    # ---- config 1: C_nat encode and decode of one vector of 2^20 elements (5 MB: bound by the launch, not by HBM)
+    d1 = 1 << 20
+    x1 = torch.from_numpy(wl.config1()).cuda()
+    e1, s1 = nc.nat_encode(x1, 0)
+    o1 = torch.empty(d1, dtype=torch.float32, device="cuda")
+    st = timer.rotating([lambda: nc.nat_encode(x1, 0, exp_out=e1, sign_out=s1)])
+    res["config1_nat_encode_d1M"] = _entry(st, 5.125 * d1, 4.0 * d1, "one launch over 5.4 MB (cache-resident, launch-bound)", 1)
+    st = timer.rotating([lambda: nc.nat_decode(e1, s1, d1, out=o1)])
+    res["config1_nat_decode_d1M"] = _entry(st, 5.125 * d1, 4.0 * d1, "one launch over 5.4 MB (cache-resident, launch-bound)", 1)
+
     # ---- C_nat decode of one worker (config 2 shape): 1.125 d read, 4 d written
     R = sets_for(5.125 * d)
     xs = [wl.layered_laplace_device(r, off) for r in range(R)]
