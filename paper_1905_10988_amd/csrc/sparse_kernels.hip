@@ -353,9 +353,10 @@ __global__ __launch_bounds__(kMoveLanes) void sparse_move_coarse_kernel(SparsePa
                          [shift](uint32_t v) { return v >> shift; }, [&](uint32_t b) { return base[b]; }, a.idx1, a.meta1);
 }
 
-// Which piece of the coarse-sorted list a workgroup of passes 4 and 6 takes: chunks of
-// kSparseChunk entries that do not cross a bin's end, numbered bin by bin.  False past the last
-// chunk (the grid is sized for the worst case; workgroup-uniform).
+// Which piece of the coarse-sorted list a workgroup of pass 4 takes: chunks of kSparseChunk
+// entries that do not cross a bin's end, numbered bin by bin (pass 6 takes the same pieces from
+// the descriptors that pass 5 leaves).  False past the last chunk (the grid is sized for the worst
+// case; workgroup-uniform).
 struct CoarsePiece {
     uint32_t bin, bin_base, begin, end, first_chunk;  // first_chunk: number of the bin's first chunk
 };
