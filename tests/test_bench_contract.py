@@ -1,0 +1,17 @@
+"""Host-side checks of bench.py's contract that need no GPU."""
+import os
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    proc = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert proc.returncode != 0
+    assert "one GPU" in proc.stderr and proc.stdout.strip() == ""
+
+
+def test_bench_never_reads_working_files():
+    src = open(os.path.join(ROOT, "bench.py")).read() + open(os.path.join(ROOT, "__graft_entry__.py")).read()
+    assert "_work" not in src and "/root/reference" not in src
