@@ -14,4 +14,4 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 
 def test_bench_never_reads_working_files():
     src = open(os.path.join(ROOT, "bench.py")).read() + open(os.path.join(ROOT, "__graft_entry__.py")).read()
-    assert "_work" not in src and "/root/reference" not in src
+    assert "_work/" not in src and '"_work"' not in src and "/root/reference" not in src
